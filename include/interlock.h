@@ -1,0 +1,171 @@
+/*
+ * interlock.h - C ABI of the single-GPU n-wise interlocking-backpropagation step
+ * for MI355X (gfx950).
+ *
+ * The library runs one training step over a stack of K Transformer components
+ * ("modules" in the paper, Sec. 3), each followed by its own auxiliary
+ * classification head: the forward pass, the K softmax cross-entropy losses, and
+ * the n-wise truncated backward in which the gradient of head j's loss travels
+ * through component j and across n-1 component boundaries and then stops (Fig. 1
+ * caption; Sec. 3, paragraph introducing n-wise interlocking backpropagation).
+ *
+ * All pointers named "device" are HIP device pointers owned by the caller.  The
+ * library allocates no device memory: parameters, gradients, the workspace and the
+ * stream come from the caller.  All work is enqueued asynchronously on
+ * il_config.stream; the caller synchronises that stream before reading results.
+ * Every function returns an il_status; nothing is printed and nothing aborts.
+ *
+ * Components and heads are numbered 1..K as in the paper.
+ */
+#ifndef INTERLOCK_H
+#define INTERLOCK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct il_ctx il_ctx; /* opaque, host memory only */
+
+typedef enum {
+  IL_OK = 0,
+  IL_E_ARG = -1,       /* NULL pointer, k outside [1,K], n outside [1,K], unknown enum */
+  IL_E_SHAPE = -2,     /* a size the kernels cannot handle (see il_init)               */
+  IL_E_STATE = -3,     /* call-order contract violated                                 */
+  IL_E_WORKSPACE = -4, /* workspace / params / grads buffer missing or too small       */
+  IL_E_HIP = -5        /* a HIP runtime call or kernel launch failed                   */
+} il_status;
+
+typedef enum {
+  IL_F32 = 0, /* parameters, GEMM operands and saved activations in fp32 */
+  IL_BF16 = 1 /* ... in bfloat16 (round to nearest even); accumulators, LayerNorm
+                 statistics, softmax, the residual stream, losses and gradients of
+                 parameters stay fp32 */
+} il_dtype;
+
+/*
+ * Which losses are credited to component k (a K x K weight table w[k][j]):
+ *  WINDOW_SUM     every head whose n-window covers k: j in [k, min(k+n-1,K)], weight 1.
+ *                 n=1 is local learning, n=K is backprop of the summed loss.
+ *  FAR_HEAD       only j = min(k+n-1,K), weight 1 (Sec. 3: module k is updated with the
+ *                 gradient of the loss n-1 modules above it).
+ *  MEAN_LOCAL_FAR 1/2 on j=k and 1/2 on j=min(k+n-1,K) (Sec. 3, the variant used for the
+ *                 Transformer experiments; App. B).
+ * Head parameters always receive the gradient of their own loss with weight 1.
+ */
+typedef enum { IL_ROUTE_WINDOW_SUM = 0, IL_ROUTE_FAR_HEAD = 1, IL_ROUTE_MEAN_LOCAL_FAR = 2 } il_route;
+
+/*
+ * Problem statement.  Each component is `blocks_per_component` pre-LN Transformer
+ * blocks:  a = x + O(Attn(QKV(LN1 x))),  x' = a + FC2(GELU(FC1(LN2 a)))  with causal
+ * attention, tanh-GELU, biased-variance LayerNorm with ln_eps inside the root.
+ * Head k is a bias-free linear map d_model -> vocab; loss k is the mean over the
+ * batch*seq positions of the natural-log cross-entropy against `targets`.
+ *
+ * Flat parameter layout (element type = dtype; every matrix row-major, y = x W + b,
+ * W is [in, out]):
+ *   for component 1..K, for block 1..L:
+ *     ln1_g[d] ln1_b[d] w_qkv[d,3d] b_qkv[3d] w_o[d,d] b_o[d]
+ *     ln2_g[d] ln2_b[d] w_fc1[d,m] b_fc1[m] w_fc2[m,d] b_fc2[d]
+ *   then heads 1..K: w_head[d,V]
+ * w_qkv's columns are Q | K | V, each split into n_heads groups of d/n_heads columns.
+ * `grads` has the same element order in fp32.  Every gradient element is overwritten
+ * exactly once per step (no zeroing needed, nothing accumulates across steps).
+ */
+typedef struct il_config {
+  int32_t K;                    /* components (= heads)                              */
+  int32_t blocks_per_component; /* L                                                 */
+  int32_t d_model, n_heads, d_mlp, vocab;
+  int32_t batch, seq;           /* N = batch*seq token rows, row index = b*seq + t   */
+  int32_t n;                    /* window, 1..K                                      */
+  int32_t dtype;                /* il_dtype                                          */
+  int32_t route;                /* il_route                                          */
+  float ln_eps;                 /* e.g. 1e-5                                         */
+  int32_t head_chunk;           /* token rows per head chunk (0 = library default);
+                                   only a [head_chunk, vocab] logits tile ever exists */
+  int32_t profile;              /* nonzero: record per-kernel-class HIP event times   */
+  void *params;                 /* device, flat layout above                         */
+  size_t params_bytes;
+  void *grads;                  /* device, fp32, same order                          */
+  size_t grads_bytes;
+  void *workspace;              /* device: saved activations, gradient streams, scratch */
+  size_t workspace_bytes;
+  void *stream;                 /* hipStream_t (NULL = the default stream)           */
+} il_config;
+
+/*
+ * Validate cfg and create a context (host memory only).
+ * Size query: call with cfg->workspace == NULL; the three *_bytes fields are filled
+ * with the required sizes, *out is left NULL and IL_E_WORKSPACE is returned.
+ * Limits: d_model % n_heads == 0; head width d/n_heads in {16, 32, 64, 128};
+ * d_model <= 2048*... see IL_E_SHAPE: d_model, d_mlp, vocab multiples of 8 and
+ * batch*seq a multiple of 64 in bf16 mode; at most 16 live gradient streams per component.
+ * The workspace must be 256-byte aligned.
+ */
+int il_init(il_config *cfg, il_ctx **out);
+
+/*
+ * Component forward x_k = f_k(x_{k-1}) (Sec. 3: the model is a composition of modules).
+ * x_in, x_out: device fp32 [N, d_model] (the residual stream is fp32 in both dtypes);
+ * they may not alias.  Saves what the backward needs in the workspace (x_in is copied,
+ * so the caller may reuse it).  k = 1 starts a new step and resets the routing state.
+ * Order: k-1 must have been run in this step (IL_E_STATE otherwise).
+ */
+int il_stage_forward(il_ctx *ctx, int32_t k, const float *x_in, float *x_out);
+
+/*
+ * Auxiliary head k and its local loss L_k = xent(h_k(x_k), y) (Sec. 3, the equation
+ * defining the local loss).  x_k: device fp32 [N, d_model]; targets: device int32 [N],
+ * each in [0, vocab); loss_out: device fp32 scalar (mean over N, natural log).
+ * Writes dL_k/dW_head,k into grads and keeps dL_k/dx_k in the workspace as the
+ * gradient stream of head k (age 0) for il_stage_backward_nwise.  Logits and
+ * probabilities exist only one [head_chunk, vocab] tile at a time.
+ * Order: after il_stage_forward(k) of the same step.
+ */
+int il_head_xent(il_ctx *ctx, int32_t k, const float *x_k, const int32_t *targets, float *loss_out);
+
+/*
+ * n-wise truncated backward through component k (Fig. 1; Sec. 3: each module runs up
+ * to n backward passes).  Every gradient stream live at x_k - the heads whose credited
+ * range reaches down to k - is carried through the component's backward; the
+ * component's parameter gradient receives sum_j w[k][j] * dL_j/dtheta_k; streams whose
+ * lowest credited component is k stop here (stop-gradient at the window edge).
+ * Call for k = K, K-1, ..., 1, after il_head_xent(j) for every head j >= k that is live
+ * at k.  dx0_out: for k == 1, optional device fp32 [N, d_model] receiving
+ * sum_j w[1][j] * dL_j/dx_0 (for the caller's embedding gradient); NULL to skip; ignored
+ * for k > 1.
+ */
+int il_stage_backward_nwise(il_ctx *ctx, int32_t k, float *dx0_out);
+
+/* Release the context (host memory and HIP events only; no device buffer is freed). */
+int il_free(il_ctx *ctx);
+
+/* ---- host-side introspection (no GPU work) ------------------------------------ */
+
+/*
+ * The routing plan for (K, n, route): for component k = 1..K, live[k-1] receives the
+ * number of gradient streams carried through component k's backward after merging
+ * streams that share their remaining route, and passes[k-1] the number of heads
+ * whose gradient passes through it (the paper's backward passes per module, Sec. 3).
+ * Either array may be NULL.  Returns IL_E_ARG for n outside [1,K] or unknown route.
+ */
+int il_routing_plan(int32_t K, int32_t n, int32_t route, int32_t *live, int32_t *passes);
+
+/*
+ * Profiling (cfg.profile != 0): synchronises the stream and returns, per kernel class,
+ * launches and total milliseconds since the last call, measured with HIP events on the
+ * library's stream.  `names` receives pointers to static strings.  Returns the number of
+ * classes written (<= cap), or a negative il_status.
+ */
+int il_profile_read(il_ctx *ctx, int32_t cap, const char **names, int64_t *launches, double *ms,
+                    double *flops, double *bytes);
+
+/* Static string for a status code. */
+const char *il_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INTERLOCK_H */

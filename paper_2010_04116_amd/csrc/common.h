@@ -1,0 +1,137 @@
+// Internal declarations shared by the HIP sources of libinterlock (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace il {
+
+typedef unsigned short bf16_t;  // raw bfloat16 bits
+
+__host__ __device__ inline float bf16_to_f32(bf16_t h) {
+  union { uint32_t u; float f; } c;
+  c.u = ((uint32_t)h) << 16;
+  return c.f;
+}
+__host__ __device__ inline bf16_t f32_to_bf16(float f) {  // round to nearest even
+  union { uint32_t u; float f; } c;
+  c.f = f;
+  uint32_t u = c.u;
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T> __device__ inline float ld(const T *p);
+template <> __device__ inline float ld<float>(const float *p) { return *p; }
+template <> __device__ inline float ld<bf16_t>(const bf16_t *p) { return bf16_to_f32(*p); }
+template <typename T> __device__ inline void st(T *p, float v);
+template <> __device__ inline void st<float>(float *p, float v) { *p = v; }
+template <> __device__ inline void st<bf16_t>(bf16_t *p, float v) { *p = f32_to_bf16(v); }
+
+// tanh-form GELU and its derivative, fp32.
+__device__ inline float gelu_f(float u) {
+  const float c = 0.7978845608028654f;
+  float t = tanhf(c * (u + 0.044715f * u * u * u));
+  return 0.5f * u * (1.0f + t);
+}
+__device__ inline float gelu_grad_f(float u) {
+  const float c = 0.7978845608028654f;
+  float t = tanhf(c * (u + 0.044715f * u * u * u));
+  return 0.5f * (1.0f + t) + 0.5f * u * (1.0f - t * t) * c * (1.0f + 0.134145f * u * u);
+}
+
+// Up to 16 gradient streams are stacked along the row dimension of the backward
+// operands; stream i occupies rows [i*N, (i+1)*N).
+constexpr int kMaxStreams = 16;
+struct StreamWeights {
+  float w[kMaxStreams];
+};
+struct SegList {  // streams that enter a weight gradient: starting row of each in the stack
+  int nseg;
+  int row0[kMaxStreams];
+};
+
+// ---- GEMM front ends (implemented in gemm_simt.hip / gemm_mfma.hip) ----------------
+enum Epi {
+  EPI_STORE = 0,      // C = acc                                  (T out)
+  EPI_BIAS = 1,       // C = acc + bias[col]                      (T out)
+  EPI_BIAS_GELU = 2,  // C = acc + bias (pre-activation, T), C2 = gelu(C) (T)
+  EPI_BIAS_RES = 3,   // Cf = acc + bias + res[row, col]          (fp32 out, fp32 residual)
+  EPI_GELU_BWD = 4,   // C = acc * gelu'(aux[row mod wrap, col])  (T out, T aux)
+  EPI_STORE_F32 = 5,  // Cf = acc                                 (fp32 out)
+  EPI_WGRAD = 6       // Cf = scale*acc (+ Cf if beta)            (fp32 out)
+};
+
+struct GemmArgs {
+  // C[M,N] = sum_k A(m,k) B(k,n); operand storage:
+  //   a_kmajor == 0: A stored [M, K] row-major (lda);  1: A stored [K, M] row-major (lda)
+  //   b_kmajor == 0: B stored [N, K] row-major (ldb);  1: B stored [K, N] row-major (ldb)
+  const void *A;
+  const void *B;
+  int M, N, K;
+  int lda, ldb;
+  int a_kmajor, b_kmajor;
+  // When a_kmajor and segs.nseg > 0 the reduction runs over nseg segments of `seg_len`
+  // rows: B rows come from segs.row0[i] + r, A rows from r (the saved activation is
+  // shared by all streams).  K must equal nseg*seg_len.
+  SegList segs;
+  int seg_len;
+  int epi;
+  void *C;        // T or fp32 depending on epi
+  void *C2;       // EPI_BIAS_GELU second output
+  int ldc;
+  const void *bias;   // T [N]
+  const float *res;   // fp32 [M, ldc]
+  const void *aux;    // T, EPI_GELU_BWD
+  int aux_wrap;       // rows of aux (row index taken modulo this)
+  float scale;        // EPI_WGRAD
+  int beta;           // EPI_WGRAD: accumulate into C
+};
+
+hipError_t gemm_f32(const GemmArgs &g, hipStream_t s);    // T = float, SIMT
+hipError_t gemm_bf16(const GemmArgs &g, hipStream_t s);   // T = bf16, MFMA
+
+// ---- row-wise kernels (layernorm.hip) -----------------------------------------------
+// y = LN(x)*gamma+beta -> T; stats[row] = (mean, rstd); optional fp32 copy of x.
+hipError_t ln_forward(int dtype, const float *x, const void *gamma, const void *beta, float eps,
+                      int rows, int d, void *y, float *stats, float *xcopy, hipStream_t s);
+// For each stacked row r (stream r / N, token r % N): G[r] += LN'(x)^T dy[r]; Gb[r] = T(G[r]);
+// partial column sums of w*dy*xhat and w*dy go to `partials` ([nblk][2*d]); returns nblk.
+hipError_t ln_backward_residual(int dtype, const void *dy, const float *x, const float *stats,
+                                const void *gamma, int rows, int N, int d, float *G, void *Gb,
+                                StreamWeights sw, float *partials, int *nblk, hipStream_t s);
+int ln_backward_max_blocks();
+
+// ---- reductions / elementwise (reduce.hip) --------------------------------------------
+// out[c] = sum over blocks p of partials[p][c], c < cols (fp32 out, deterministic order)
+hipError_t colsum_final(const float *partials, int nblk, int cols, float *out, int accumulate, hipStream_t s);
+// partials[p][c] = sum over rows of block p of w(stream(row)) * Y[row][c]; returns nblk
+hipError_t colsum_partial(int dtype, const void *Y, int rows, int N, int cols, int ld, StreamWeights sw,
+                          float *partials, int *nblk, hipStream_t s);
+int colsum_max_blocks();
+// G[i] = (accumulate ? G[i] : 0) + src[i]; Gb[i] = T(G[i])
+hipError_t stream_inject(int dtype, const float *src, float *G, void *Gb, size_t count, int accumulate,
+                         hipStream_t s);
+// out[i] = (accumulate ? out[i] : 0) + sum_j w[j] * G[j*stride + i]
+hipError_t stream_combine(const float *G, size_t stride, int nstreams, StreamWeights sw, float *out,
+                          size_t count, int accumulate, hipStream_t s);
+// dst = T(src)
+hipError_t convert_f32(int dtype, const float *src, void *dst, size_t count, hipStream_t s);
+
+// ---- attention (attention_*.hip) --------------------------------------------------------
+// qkv: T [N, 3d] (Q|K|V, heads contiguous); o: T [N, d]; lse: fp32 [B, H, T]
+hipError_t attention_forward(int dtype, const void *qkv, int B, int T, int H, int dh, void *o, float *lse,
+                             hipStream_t s);
+// d_o: T [nstreams*N, d]; dqkv: T [nstreams*N, 3d]; dsum: fp32 scratch [nstreams*N*H]
+hipError_t attention_backward(int dtype, const void *qkv, const void *o, const void *d_o, const float *lse,
+                              int nstreams, int B, int T, int H, int dh, void *dqkv, float *dsum,
+                              hipStream_t s);
+
+// ---- cross-entropy rows (xent.hip) --------------------------------------------------------
+// For each of `rows` logit rows z (T, [rows, V], in place): rowloss = lse - z[target];
+// z <- (softmax(z) - onehot(target)) * inv_n.
+hipError_t xent_rows(int dtype, void *z, const int32_t *targets, int rows, int V, float inv_n,
+                     float *rowloss, hipStream_t s);
+// loss_out[0] = scale * sum(rowloss[0..rows))
+hipError_t sum_scalar(const float *rowloss, int rows, float scale, float *loss_out, hipStream_t s);
+
+}  // namespace il

@@ -1,0 +1,629 @@
+// libinterlock: context, routing plan, workspace layout and the C-ABI entry points.
+// The step is K x (il_stage_forward, il_head_xent) followed by il_stage_backward_nwise
+// for k = K..1.  Gradient streams (one per head, merged where they share their remaining
+// route) live in fp32 "slots" ordered by the lowest component they reach.  Under the
+// window-sum and far-head routings the streams live at any component occupy adjacent
+// slots, i.e. one contiguous stack [cnt*N, d], and every backward GEMM processes all of
+// them in a single launch; where the live slots are not adjacent the component's backward
+// runs once per contiguous range and the later ranges accumulate.
+#include "../../include/interlock.h"
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "common.h"
+
+using namespace il;
+
+namespace il {
+hipError_t attention_forward_simt(int, const void *, int, int, int, int, void *, float *, hipStream_t);
+hipError_t attention_backward_simt(int, const void *, const void *, const void *, const float *, int, int, int,
+                                   int, int, void *, float *, hipStream_t);
+}  // namespace il
+
+namespace {
+
+// ------------------------------------------------------------------ routing plan ----
+struct StreamDesc {
+  int lo, hi;  // lowest / highest component the stream passes through (1-based)
+};
+struct Run {                    // a contiguous range of live slots, processed as one stack
+  int s0 = 0, cnt = 0;          // slots [s0, s0+cnt)
+  float wt[kMaxStreams] = {};   // routing weight of each stream at this component
+  SegList segs = {};            // streams with non-zero weight (stream index; times N at launch)
+  float wscale = 1.f;           // their common weight
+  int acc = 0;                  // 1: parameter gradients add to what an earlier run wrote
+};
+struct CompPlan {
+  std::vector<Run> runs;        // usually one; several only when the live slots are not adjacent
+  int cnt = 0;                  // live streams in total
+  int inject_slot = -1;         // slot head k's fresh gradient joins, -1: head k is not used
+  int inject_acc = 0;           // 1: add to the stream already in the slot
+  int passes = 0;               // heads whose gradient passes through this component
+};
+struct Plan {
+  int K = 0, nslots = 0, maxcnt = 0;
+  std::vector<StreamDesc> streams;
+  std::vector<CompPlan> comp;   // index k-1
+};
+
+int route_weights(int K, int n, int route, std::vector<double> &w) {
+  if (K < 1 || n < 1 || n > K) return IL_E_ARG;
+  w.assign((size_t)K * K, 0.0);
+  for (int k = 1; k <= K; ++k) {
+    const int far = std::min(k + n - 1, K);
+    switch (route) {
+      case IL_ROUTE_WINDOW_SUM:
+        for (int j = k; j <= far; ++j) w[(k - 1) * K + j - 1] = 1.0;
+        break;
+      case IL_ROUTE_FAR_HEAD: w[(k - 1) * K + far - 1] = 1.0; break;
+      case IL_ROUTE_MEAN_LOCAL_FAR:
+        w[(k - 1) * K + k - 1] += 0.5;
+        w[(k - 1) * K + far - 1] += 0.5;
+        break;
+      default: return IL_E_ARG;
+    }
+  }
+  return IL_OK;
+}
+
+int build_plan(int K, int n, int route, Plan &p) {
+  std::vector<double> w;
+  int rc = route_weights(K, n, route, w);
+  if (rc) return rc;
+  auto W = [&](int k, int j) { return w[(size_t)(k - 1) * K + j - 1]; };
+  p = Plan();
+  p.K = K;
+  p.comp.assign(K, CompPlan());
+  std::vector<int> lo(K + 1, 0), group(K + 1, -1);
+  for (int j = 1; j <= K; ++j)
+    for (int k = 1; k <= j; ++k)
+      if (W(k, j) != 0.0) { lo[j] = k; break; }
+  // group heads top-down: head j joins a stream created by a higher head when both stop at
+  // the same component and carry the same weights over every component they share
+  struct G { int lo, hi; };
+  std::vector<G> groups;
+  for (int j = K; j >= 1; --j) {
+    if (!lo[j]) continue;
+    int found = -1;
+    for (size_t g = 0; g < groups.size() && found < 0; ++g) {
+      if (groups[g].lo != lo[j]) continue;
+      bool same = true;
+      for (int k = lo[j]; k <= j; ++k) same = same && (W(k, j) == W(k, groups[g].hi));
+      if (same) found = (int)g;
+    }
+    if (found < 0) { groups.push_back({lo[j], j}); found = (int)groups.size() - 1; }
+    group[j] = found;
+  }
+  // slots: ascending (lo, hi)
+  std::vector<int> order(groups.size());
+  for (size_t i = 0; i < order.size(); ++i) order[i] = (int)i;
+  for (size_t a = 0; a < order.size(); ++a)
+    for (size_t b = a + 1; b < order.size(); ++b) {
+      const G &x = groups[order[a]], &y = groups[order[b]];
+      if (y.lo < x.lo || (y.lo == x.lo && y.hi < x.hi)) std::swap(order[a], order[b]);
+    }
+  std::vector<int> slot_of(groups.size());
+  for (size_t s = 0; s < order.size(); ++s) {
+    slot_of[order[s]] = (int)s;
+    p.streams.push_back({groups[order[s]].lo, groups[order[s]].hi});
+  }
+  p.nslots = (int)groups.size();
+  for (int k = 1; k <= K; ++k) {
+    CompPlan &c = p.comp[k - 1];
+    bool written = false;
+    for (int s = 0; s < p.nslots; ++s) {
+      if (!(p.streams[s].lo <= k && k <= p.streams[s].hi)) continue;
+      if (c.runs.empty() || c.runs.back().s0 + c.runs.back().cnt != s || c.runs.back().cnt == kMaxStreams) {
+        Run r;
+        r.s0 = s;
+        c.runs.push_back(r);
+      }
+      Run &r = c.runs.back();
+      const float wt = (float)W(k, p.streams[s].hi);
+      if (wt != 0.f && r.segs.nseg && wt != r.wscale) {  // one stack shares one weight-gradient scale
+        Run r2;
+        r2.s0 = s;
+        c.runs.push_back(r2);
+      }
+      Run &q = c.runs.back();
+      q.wt[q.cnt] = wt;
+      if (wt != 0.f) {
+        q.wscale = wt;
+        q.segs.row0[q.segs.nseg++] = q.cnt;
+      }
+      ++q.cnt;
+      ++c.cnt;
+    }
+    for (Run &r : c.runs) {
+      p.maxcnt = std::max(p.maxcnt, r.cnt);
+      if (r.segs.nseg) { r.acc = written; written = true; }
+    }
+    if (!written) return IL_E_ARG;  // a component no loss is credited to
+    for (int j = k; j <= K; ++j)
+      if (lo[j] && lo[j] <= k) ++c.passes;
+    if (lo[k]) {
+      c.inject_slot = slot_of[group[k]];
+      c.inject_acc = (groups[group[k]].hi != k);
+    }
+  }
+  return IL_OK;
+}
+
+// ------------------------------------------------------------------ context --------
+enum KClass { KC_GEMM_FWD, KC_GEMM_DGRAD, KC_GEMM_WGRAD, KC_GEMM_HEAD, KC_ATTN_FWD, KC_ATTN_BWD, KC_LN_FWD,
+              KC_LN_BWD, KC_COLSUM, KC_XENT, KC_MISC, KC_COUNT };
+const char *kClassNames[KC_COUNT] = {"gemm_fwd", "gemm_dgrad", "gemm_wgrad", "gemm_head", "attn_fwd", "attn_bwd",
+                                     "ln_fwd",   "ln_bwd",     "colsum",     "xent",      "misc"};
+
+struct BlockOff {  // element offsets inside the flat parameter / gradient buffers
+  size_t ln1_g, ln1_b, w_qkv, b_qkv, w_o, b_o, ln2_g, ln2_b, w_fc1, b_fc1, w_fc2, b_fc2;
+};
+struct BlockSave {  // workspace pointers of one block's saved activations
+  float *xs, *st1, *lse, *a, *st2;
+  char *h1, *qkv, *o, *h2, *u, *gl;
+};
+struct ProfRec { int cls; hipEvent_t e0, e1; };
+
+}  // namespace
+
+struct il_ctx {
+  il_config cfg;
+  Plan plan;
+  int N, d, m, V, H, dh, L, K, eb;
+  hipStream_t stream;
+  std::vector<BlockOff> boff;      // K*L
+  std::vector<size_t> hoff;        // K
+  std::vector<BlockSave> save;     // K*L
+  float *G; char *Gb;              // stream slots [nslots][N,d]
+  char *DU, *DH, *DQKV; float *dsum, *partials;
+  char *xb, *Z; float *rowloss, *dxh;
+  int Nc;
+  std::vector<char> fwd_done, head_done, bwd_done;
+  // profiling
+  std::vector<ProfRec> recs; size_t nrec = 0;
+  double flops[KC_COUNT] = {}, bytes[KC_COUNT] = {};
+};
+
+namespace {
+
+struct Carver {
+  char *base; size_t off = 0;
+  explicit Carver(void *b) : base((char *)b) {}
+  void *take(size_t bytes) {
+    void *p = base ? base + off : nullptr;
+    off += (bytes + 255) & ~(size_t)255;
+    return p;
+  }
+};
+
+size_t layout_params(il_ctx *c) {
+  const size_t d = c->d, m = c->m;
+  size_t o = 0;
+  c->boff.resize((size_t)c->K * c->L);
+  for (auto &b : c->boff) {
+    b.ln1_g = o; o += d; b.ln1_b = o; o += d; b.w_qkv = o; o += 3 * d * d; b.b_qkv = o; o += 3 * d;
+    b.w_o = o; o += d * d; b.b_o = o; o += d; b.ln2_g = o; o += d; b.ln2_b = o; o += d;
+    b.w_fc1 = o; o += d * m; b.b_fc1 = o; o += m; b.w_fc2 = o; o += m * d; b.b_fc2 = o; o += d;
+  }
+  c->hoff.resize(c->K);
+  for (auto &h : c->hoff) { h = o; o += d * (size_t)c->V; }
+  return o;
+}
+
+size_t layout_workspace(il_ctx *c, void *base) {
+  Carver cv(base);
+  const size_t N = c->N, d = c->d, m = c->m, eb = c->eb, H = c->H;
+  c->save.resize((size_t)c->K * c->L);
+  for (auto &s : c->save) {
+    s.xs = (float *)cv.take(N * d * 4); s.st1 = (float *)cv.take(N * 2 * 4);
+    s.h1 = (char *)cv.take(N * d * eb); s.qkv = (char *)cv.take(N * 3 * d * eb);
+    s.lse = (float *)cv.take(N * H * 4); s.o = (char *)cv.take(N * d * eb);
+    s.a = (float *)cv.take(N * d * 4); s.st2 = (float *)cv.take(N * 2 * 4);
+    s.h2 = (char *)cv.take(N * d * eb); s.u = (char *)cv.take(N * m * eb); s.gl = (char *)cv.take(N * m * eb);
+  }
+  const size_t ns = c->plan.nslots, S = (size_t)c->plan.maxcnt * N;
+  c->G = (float *)cv.take(ns * N * d * 4);
+  c->Gb = (c->eb == 4) ? (char *)c->G : (char *)cv.take(ns * N * d * eb);
+  c->DU = (char *)cv.take(S * m * eb);
+  c->DH = (char *)cv.take(S * d * eb);
+  c->DQKV = (char *)cv.take(S * 3 * d * eb);
+  c->dsum = (float *)cv.take(S * H * 4);
+  size_t pcols = std::max((size_t)3 * d, m);
+  size_t pbytes = std::max((size_t)ln_backward_max_blocks() * 2 * d, (size_t)colsum_max_blocks() * pcols) * 4;
+  c->partials = (float *)cv.take(pbytes);
+  c->xb = (char *)cv.take(N * d * eb);
+  c->Z = (char *)cv.take((size_t)c->Nc * c->V * eb);
+  c->rowloss = (float *)cv.take(N * 4);
+  c->dxh = (float *)cv.take((size_t)c->K * N * d * 4);
+  return cv.off;
+}
+
+// --- launch bookkeeping -----------------------------------------------------------------
+struct Scope {  // brackets a group of launches with events when profiling is on
+  il_ctx *c; int cls; ProfRec *r = nullptr;
+  Scope(il_ctx *ctx, int cls_, double flops, double bytes) : c(ctx), cls(cls_) {
+    if (!c->cfg.profile) return;
+    c->flops[cls] += flops; c->bytes[cls] += bytes;
+    if (c->nrec == c->recs.size()) {
+      ProfRec n{};
+      if (hipEventCreate(&n.e0) != hipSuccess || hipEventCreate(&n.e1) != hipSuccess) return;
+      c->recs.push_back(n);
+    }
+    r = &c->recs[c->nrec++];
+    r->cls = cls;
+    hipEventRecord(r->e0, c->stream);
+  }
+  ~Scope() { if (r) hipEventRecord(r->e1, c->stream); }
+};
+
+#define IL_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return IL_E_HIP; } while (0)
+
+hipError_t gemm(il_ctx *c, const GemmArgs &g) {
+  return c->cfg.dtype == IL_F32 ? gemm_f32(g, c->stream) : gemm_bf16(g, c->stream);
+}
+
+inline const char *P(il_ctx *c, size_t off) { return (const char *)c->cfg.params + off * c->eb; }
+inline float *Gr(il_ctx *c, size_t off) { return (float *)c->cfg.grads + off; }
+
+GemmArgs base_args() {
+  GemmArgs g;
+  memset(&g, 0, sizeof(g));
+  g.scale = 1.f;
+  return g;
+}
+
+// y[M,N] = x[M,K] W[K,N] (+ epilogue)
+int linear_fwd(il_ctx *c, const void *x, size_t w_off, size_t b_off, int M, int Kd, int Nn, int epi, void *out,
+               void *out2, const float *res) {
+  GemmArgs g = base_args();
+  g.A = x; g.lda = Kd; g.a_kmajor = 0;
+  g.B = P(c, w_off); g.ldb = Nn; g.b_kmajor = 1;
+  g.M = M; g.N = Nn; g.K = Kd; g.epi = epi; g.C = out; g.C2 = out2; g.ldc = Nn;
+  g.bias = P(c, b_off); g.res = res;
+  Scope sc(c, KC_GEMM_FWD, 2.0 * M * Nn * Kd, 0);
+  IL_TRY(gemm(c, g));
+  return IL_OK;
+}
+
+// dx[M,Kin] = dy[M,Nout] W[Kin,Nout]^T
+int linear_dgrad(il_ctx *c, const void *dy, size_t w_off, int M, int Kin, int Nout, int epi, void *out,
+                 const void *aux, int aux_wrap) {
+  GemmArgs g = base_args();
+  g.A = dy; g.lda = Nout; g.a_kmajor = 0;
+  g.B = P(c, w_off); g.ldb = Nout; g.b_kmajor = 0;
+  g.M = M; g.N = Kin; g.K = Nout; g.epi = epi; g.C = out; g.ldc = Kin; g.aux = aux; g.aux_wrap = aux_wrap;
+  Scope sc(c, KC_GEMM_DGRAD, 2.0 * M * Kin * Nout, 0);
+  IL_TRY(gemm(c, g));
+  return IL_OK;
+}
+
+// dW[Kin,Nout] = scale * sum over included streams of x[N,Kin]^T dy_s[N,Nout];  db = weighted column sums
+int linear_wgrad(il_ctx *c, const Run &cp, const void *x, const void *dy, int Kin, int Nout, size_t w_off,
+                 size_t b_off) {
+  if (cp.segs.nseg == 0) return IL_OK;  // pass-through streams only: nothing is credited
+  GemmArgs g = base_args();
+  g.A = x; g.lda = Kin; g.a_kmajor = 1;
+  g.B = dy; g.ldb = Nout; g.b_kmajor = 1;
+  g.M = Kin; g.N = Nout; g.segs = cp.segs; g.seg_len = c->N;
+  for (int i = 0; i < g.segs.nseg; ++i) g.segs.row0[i] *= c->N;
+  g.K = g.segs.nseg * c->N;
+  g.epi = EPI_WGRAD; g.C = Gr(c, w_off); g.ldc = Nout; g.scale = cp.wscale; g.beta = cp.acc;
+  {
+    Scope sc(c, KC_GEMM_WGRAD, 2.0 * g.K * Kin * Nout, 0);
+    IL_TRY(gemm(c, g));
+  }
+  StreamWeights sw;
+  memcpy(sw.w, cp.wt, sizeof(sw.w));
+  int nblk = 0;
+  const int rows = cp.cnt * c->N;
+  Scope sc(c, KC_COLSUM, 0, (double)rows * Nout * c->eb);
+  IL_TRY(colsum_partial(c->cfg.dtype, dy, rows, c->N, Nout, Nout, sw, c->partials, &nblk, c->stream));
+  IL_TRY(colsum_final(c->partials, nblk, Nout, Gr(c, b_off), cp.acc, c->stream));
+  return IL_OK;
+}
+
+int attention_fwd(il_ctx *c, const void *qkv, void *o, float *lse) {
+  Scope sc(c, KC_ATTN_FWD, 2.0 * c->cfg.batch * (double)c->cfg.seq * c->cfg.seq * c->d, 0);
+  IL_TRY(attention_forward(c->cfg.dtype, qkv, c->cfg.batch, c->cfg.seq, c->H, c->dh, o, lse, c->stream));
+  return IL_OK;
+}
+
+int attention_bwd(il_ctx *c, const BlockSave &s, const void *d_o, int cnt, void *dqkv) {
+  Scope sc(c, KC_ATTN_BWD, 5.0 * cnt * c->cfg.batch * (double)c->cfg.seq * c->cfg.seq * c->d, 0);
+  IL_TRY(attention_backward(c->cfg.dtype, s.qkv, s.o, d_o, s.lse, cnt, c->cfg.batch, c->cfg.seq, c->H, c->dh,
+                            dqkv, c->dsum, c->stream));
+  return IL_OK;
+}
+
+int ln_bwd(il_ctx *c, const Run &cp, const void *dy, const float *x, const float *stats, size_t g_off,
+           float *G, void *Gb) {
+  StreamWeights sw;
+  memcpy(sw.w, cp.wt, sizeof(sw.w));
+  const int rows = cp.cnt * c->N;
+  int nblk = 0;
+  Scope sc(c, KC_LN_BWD, 0, (double)rows * c->d * (c->eb + 8 + c->eb) + (double)c->N * c->d * 4);
+  IL_TRY(ln_backward_residual(c->cfg.dtype, dy, x, stats, P(c, g_off), rows, c->N, c->d, G, Gb, sw, c->partials,
+                              &nblk, c->stream));
+  if (cp.segs.nseg) IL_TRY(colsum_final(c->partials, nblk, 2 * c->d, Gr(c, g_off), cp.acc, c->stream));
+  return IL_OK;
+}
+
+int block_forward(il_ctx *c, const BlockOff &b, const BlockSave &s, const float *x, float *xcopy, float *x_out) {
+  const int N = c->N, d = c->d, m = c->m, dt = c->cfg.dtype;
+  {
+    Scope sc(c, KC_LN_FWD, 0, (double)N * d * (4 + c->eb));
+    IL_TRY(ln_forward(dt, x, P(c, b.ln1_g), P(c, b.ln1_b), c->cfg.ln_eps, N, d, s.h1, s.st1, xcopy, c->stream));
+  }
+  int rc;
+  if ((rc = linear_fwd(c, s.h1, b.w_qkv, b.b_qkv, N, d, 3 * d, EPI_BIAS, s.qkv, nullptr, nullptr))) return rc;
+  if ((rc = attention_fwd(c, s.qkv, s.o, s.lse))) return rc;
+  if ((rc = linear_fwd(c, s.o, b.w_o, b.b_o, N, d, d, EPI_BIAS_RES, s.a, nullptr, x))) return rc;
+  {
+    Scope sc(c, KC_LN_FWD, 0, (double)N * d * (4 + c->eb));
+    IL_TRY(ln_forward(dt, s.a, P(c, b.ln2_g), P(c, b.ln2_b), c->cfg.ln_eps, N, d, s.h2, s.st2, nullptr,
+                      c->stream));
+  }
+  if ((rc = linear_fwd(c, s.h2, b.w_fc1, b.b_fc1, N, d, m, EPI_BIAS_GELU, s.u, s.gl, nullptr))) return rc;
+  if ((rc = linear_fwd(c, s.gl, b.w_fc2, b.b_fc2, N, m, d, EPI_BIAS_RES, x_out, nullptr, s.a))) return rc;
+  return IL_OK;
+}
+
+int block_backward(il_ctx *c, const Run &cp, const BlockOff &b, const BlockSave &s) {
+  const int N = c->N, d = c->d, m = c->m;
+  const int S = cp.cnt * N;
+  float *G = c->G + (size_t)cp.s0 * N * d;
+  char *Gb = c->Gb + (size_t)cp.s0 * N * d * c->eb;
+  int rc;
+  // MLP
+  if ((rc = linear_dgrad(c, Gb, b.w_fc2, S, m, d, EPI_GELU_BWD, c->DU, s.u, N))) return rc;
+  if ((rc = linear_wgrad(c, cp, s.gl, Gb, m, d, b.w_fc2, b.b_fc2))) return rc;
+  if ((rc = linear_wgrad(c, cp, s.h2, c->DU, d, m, b.w_fc1, b.b_fc1))) return rc;
+  if ((rc = linear_dgrad(c, c->DU, b.w_fc1, S, d, m, EPI_STORE, c->DH, nullptr, 0))) return rc;
+  if ((rc = ln_bwd(c, cp, c->DH, s.a, s.st2, b.ln2_g, G, Gb))) return rc;
+  // attention
+  if ((rc = linear_wgrad(c, cp, s.o, Gb, d, d, b.w_o, b.b_o))) return rc;
+  if ((rc = linear_dgrad(c, Gb, b.w_o, S, d, d, EPI_STORE, c->DH, nullptr, 0))) return rc;
+  if ((rc = attention_bwd(c, s, c->DH, cp.cnt, c->DQKV))) return rc;
+  if ((rc = linear_wgrad(c, cp, s.h1, c->DQKV, d, 3 * d, b.w_qkv, b.b_qkv))) return rc;
+  if ((rc = linear_dgrad(c, c->DQKV, b.w_qkv, S, d, 3 * d, EPI_STORE, c->DH, nullptr, 0))) return rc;
+  if ((rc = ln_bwd(c, cp, c->DH, s.xs, s.st1, b.ln1_g, G, Gb))) return rc;
+  return IL_OK;
+}
+
+int validate(const il_config *cfg) {
+  if (cfg->K < 1 || cfg->blocks_per_component < 1 || cfg->d_model < 1 || cfg->n_heads < 1 || cfg->d_mlp < 1 ||
+      cfg->vocab < 2 || cfg->batch < 1 || cfg->seq < 1)
+    return IL_E_ARG;
+  if (cfg->n < 1 || cfg->n > cfg->K) return IL_E_ARG;
+  if (cfg->dtype != IL_F32 && cfg->dtype != IL_BF16) return IL_E_ARG;
+  if (cfg->route < 0 || cfg->route > IL_ROUTE_MEAN_LOCAL_FAR) return IL_E_ARG;
+  if (!(cfg->ln_eps > 0.f)) return IL_E_ARG;
+  if (cfg->head_chunk < 0) return IL_E_ARG;
+  if (cfg->d_model % cfg->n_heads) return IL_E_SHAPE;
+  const int dh = cfg->d_model / cfg->n_heads;
+  if (dh != 16 && dh != 32 && dh != 64 && dh != 128) return IL_E_SHAPE;
+  if (cfg->d_model > 2048) return IL_E_SHAPE;
+  const long long N = (long long)cfg->batch * cfg->seq;
+  if (N > (1 << 24) || (long long)cfg->vocab > (1 << 24)) return IL_E_SHAPE;
+  if (cfg->dtype == IL_BF16) {
+    if (cfg->d_model % 8 || cfg->d_mlp % 8 || cfg->vocab % 8 || N % 64) return IL_E_SHAPE;
+    if (cfg->head_chunk % 64) return IL_E_SHAPE;
+  }
+  return IL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *il_status_string(int status) {
+  switch (status) {
+    case IL_OK: return "IL_OK";
+    case IL_E_ARG: return "IL_E_ARG: invalid argument";
+    case IL_E_SHAPE: return "IL_E_SHAPE: size not supported by the kernels";
+    case IL_E_STATE: return "IL_E_STATE: call order violated";
+    case IL_E_WORKSPACE: return "IL_E_WORKSPACE: buffer missing or too small";
+    case IL_E_HIP: return "IL_E_HIP: HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+int il_routing_plan(int32_t K, int32_t n, int32_t route, int32_t *live, int32_t *passes) {
+  Plan p;
+  int rc = build_plan(K, n, route, p);
+  if (rc) return rc;
+  for (int k = 0; k < K; ++k) {
+    if (live) live[k] = p.comp[k].cnt;
+    if (passes) passes[k] = p.comp[k].passes;
+  }
+  return IL_OK;
+}
+
+int il_init(il_config *cfg, il_ctx **out) {
+  if (!cfg || !out) return IL_E_ARG;
+  *out = nullptr;
+  int rc = validate(cfg);
+  if (rc) return rc;
+  il_ctx *c = new (std::nothrow) il_ctx();
+  if (!c) return IL_E_ARG;
+  c->cfg = *cfg;
+  c->K = cfg->K; c->L = cfg->blocks_per_component; c->d = cfg->d_model; c->m = cfg->d_mlp; c->V = cfg->vocab;
+  c->H = cfg->n_heads; c->dh = c->d / c->H; c->N = cfg->batch * cfg->seq;
+  c->eb = cfg->dtype == IL_F32 ? 4 : 2;
+  c->stream = (hipStream_t)cfg->stream;
+  rc = build_plan(c->K, cfg->n, cfg->route, c->plan);
+  if (rc) { delete c; return rc; }
+  int nc = cfg->head_chunk;
+  if (nc == 0) {
+    nc = std::min(c->N / 2, 2048);
+    if (cfg->dtype == IL_BF16) nc = (nc / 64) * 64;
+    if (nc < 1) nc = c->N;
+    if (cfg->dtype == IL_BF16 && nc < 64) nc = 64;
+  }
+  c->Nc = std::min(nc, c->N);
+  const size_t pbytes = layout_params(c) * c->eb;
+  const size_t gbytes = pbytes / c->eb * 4;
+  const size_t wbytes = layout_workspace(c, cfg->workspace);
+  if (!cfg->workspace) {
+    cfg->params_bytes = pbytes; cfg->grads_bytes = gbytes; cfg->workspace_bytes = wbytes;
+    delete c;
+    return IL_E_WORKSPACE;
+  }
+  if (!cfg->params || !cfg->grads || cfg->params_bytes < pbytes || cfg->grads_bytes < gbytes ||
+      cfg->workspace_bytes < wbytes || ((uintptr_t)cfg->workspace & 255) || ((uintptr_t)cfg->params & 15) ||
+      ((uintptr_t)cfg->grads & 15)) {
+    delete c;
+    return IL_E_WORKSPACE;
+  }
+  c->fwd_done.assign(c->K + 1, 0); c->head_done.assign(c->K + 1, 0); c->bwd_done.assign(c->K + 2, 0);
+  *out = c;
+  return IL_OK;
+}
+
+int il_stage_forward(il_ctx *c, int32_t k, const float *x_in, float *x_out) {
+  if (!c || !x_in || !x_out || x_in == x_out) return IL_E_ARG;
+  if (k < 1 || k > c->K) return IL_E_ARG;
+  if (k == 1) {
+    std::fill(c->fwd_done.begin(), c->fwd_done.end(), 0);
+    std::fill(c->head_done.begin(), c->head_done.end(), 0);
+    std::fill(c->bwd_done.begin(), c->bwd_done.end(), 0);
+  } else if (!c->fwd_done[k - 1]) {
+    return IL_E_STATE;
+  }
+  for (int l = 0; l < c->L; ++l) {
+    const size_t bi = (size_t)(k - 1) * c->L + l;
+    const BlockSave &s = c->save[bi];
+    const float *xin = l == 0 ? x_in : s.xs;
+    float *xout = l == c->L - 1 ? x_out : c->save[bi + 1].xs;
+    int rc = block_forward(c, c->boff[bi], s, xin, l == 0 ? s.xs : nullptr, xout);
+    if (rc) return rc;
+  }
+  c->fwd_done[k] = 1;
+  c->head_done[k] = 0;
+  return IL_OK;
+}
+
+int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets, float *loss_out) {
+  if (!c || !x_k || !targets || !loss_out) return IL_E_ARG;
+  if (k < 1 || k > c->K) return IL_E_ARG;
+  if (!c->fwd_done[k]) return IL_E_STATE;
+  const int N = c->N, d = c->d, V = c->V, dt = c->cfg.dtype;
+  const size_t eb = c->eb;
+  {
+    Scope sc(c, KC_MISC, 0, (double)N * d * (4 + eb));
+    IL_TRY(convert_f32(dt, x_k, c->xb, (size_t)N * d, c->stream));
+  }
+  float *dx = c->dxh + (size_t)(k - 1) * N * d;
+  for (int r0 = 0, chunk = 0; r0 < N; r0 += c->Nc, ++chunk) {
+    const int rows = std::min(c->Nc, N - r0);
+    const char *xc = c->xb + (size_t)r0 * d * eb;
+    GemmArgs g = base_args();  // logits tile z = x W_h
+    g.A = xc; g.lda = d; g.a_kmajor = 0;
+    g.B = P(c, c->hoff[k - 1]); g.ldb = V; g.b_kmajor = 1;
+    g.M = rows; g.N = V; g.K = d; g.epi = EPI_STORE; g.C = c->Z; g.ldc = V;
+    {
+      Scope sc(c, KC_GEMM_HEAD, 2.0 * rows * V * d, 0);
+      IL_TRY(gemm(c, g));
+    }
+    {
+      Scope sc(c, KC_XENT, 0, 2.0 * rows * V * eb);
+      IL_TRY(xent_rows(dt, c->Z, targets + r0, rows, V, 1.f / N, c->rowloss + r0, c->stream));
+    }
+    g = base_args();  // dx = dz W_h^T
+    g.A = c->Z; g.lda = V; g.a_kmajor = 0;
+    g.B = P(c, c->hoff[k - 1]); g.ldb = V; g.b_kmajor = 0;
+    g.M = rows; g.N = d; g.K = V; g.epi = EPI_STORE_F32; g.C = dx + (size_t)r0 * d; g.ldc = d;
+    {
+      Scope sc(c, KC_GEMM_HEAD, 2.0 * rows * V * d, 0);
+      IL_TRY(gemm(c, g));
+    }
+    g = base_args();  // dW_h (+)= x^T dz
+    g.A = xc; g.lda = d; g.a_kmajor = 1;
+    g.B = c->Z; g.ldb = V; g.b_kmajor = 1;
+    g.M = d; g.N = V; g.K = rows; g.epi = EPI_WGRAD; g.C = Gr(c, c->hoff[k - 1]); g.ldc = V;
+    g.beta = chunk > 0;
+    {
+      Scope sc(c, KC_GEMM_HEAD, 2.0 * rows * V * d, 0);
+      IL_TRY(gemm(c, g));
+    }
+  }
+  {
+    Scope sc(c, KC_MISC, 0, (double)N * 4);
+    IL_TRY(sum_scalar(c->rowloss, N, 1.f, loss_out, c->stream));
+  }
+  c->head_done[k] = 1;
+  return IL_OK;
+}
+
+int il_stage_backward_nwise(il_ctx *c, int32_t k, float *dx0_out) {
+  if (!c) return IL_E_ARG;
+  if (k < 1 || k > c->K) return IL_E_ARG;
+  for (int j = 1; j <= c->K; ++j)
+    if (!c->fwd_done[j]) return IL_E_STATE;
+  if (c->bwd_done[k] || (k < c->K && !c->bwd_done[k + 1])) return IL_E_STATE;
+  const CompPlan &cp = c->plan.comp[k - 1];
+  if (cp.inject_slot >= 0 && !c->head_done[k]) return IL_E_STATE;
+  const size_t nd = (size_t)c->N * c->d;
+  if (cp.inject_slot >= 0) {
+    Scope sc(c, KC_MISC, 0, (double)nd * (8 + c->eb));
+    IL_TRY(stream_inject(c->cfg.dtype, c->dxh + (size_t)(k - 1) * nd, c->G + cp.inject_slot * nd,
+                         c->Gb + cp.inject_slot * nd * c->eb, nd, cp.inject_acc, c->stream));
+  }
+  for (int l = c->L - 1; l >= 0; --l) {
+    const size_t bi = (size_t)(k - 1) * c->L + l;
+    for (const Run &r : cp.runs) {
+      int rc = block_backward(c, r, c->boff[bi], c->save[bi]);
+      if (rc) return rc;
+    }
+  }
+  if (k == 1 && dx0_out) {
+    Scope sc(c, KC_MISC, 0, (double)nd * 4 * (cp.cnt + 1));
+    for (size_t i = 0; i < cp.runs.size(); ++i) {
+      const Run &r = cp.runs[i];
+      StreamWeights sw;
+      memcpy(sw.w, r.wt, sizeof(sw.w));
+      IL_TRY(stream_combine(c->G + r.s0 * nd, nd, r.cnt, sw, dx0_out, nd, i > 0, c->stream));
+    }
+  }
+  c->bwd_done[k] = 1;
+  return IL_OK;
+}
+
+int il_profile_read(il_ctx *c, int32_t cap, const char **names, int64_t *launches, double *ms, double *flops,
+                    double *bytes) {
+  if (!c || cap < 0) return IL_E_ARG;
+  if (hipStreamSynchronize(c->stream) != hipSuccess) return IL_E_HIP;
+  double t[KC_COUNT] = {};
+  int64_t n[KC_COUNT] = {};
+  for (size_t i = 0; i < c->nrec; ++i) {
+    float e = 0.f;
+    if (hipEventElapsedTime(&e, c->recs[i].e0, c->recs[i].e1) != hipSuccess) return IL_E_HIP;
+    t[c->recs[i].cls] += e;
+    n[c->recs[i].cls] += 1;
+  }
+  const int cnt = std::min<int>(cap, KC_COUNT);
+  for (int i = 0; i < cnt; ++i) {
+    if (names) names[i] = kClassNames[i];
+    if (launches) launches[i] = n[i];
+    if (ms) ms[i] = t[i];
+    if (flops) flops[i] = c->flops[i];
+    if (bytes) bytes[i] = c->bytes[i];
+  }
+  c->nrec = 0;
+  memset(c->flops, 0, sizeof(c->flops));
+  memset(c->bytes, 0, sizeof(c->bytes));
+  return cnt;
+}
+
+int il_free(il_ctx *c) {
+  if (!c) return IL_E_ARG;
+  for (auto &r : c->recs) { hipEventDestroy(r.e0); hipEventDestroy(r.e1); }
+  delete c;
+  return IL_OK;
+}
+
+}  // extern "C"

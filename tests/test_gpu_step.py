@@ -1,0 +1,119 @@
+"""GPU parity of the whole n-wise step against the float64 oracle, through the C ABI."""
+import sys
+
+import numpy as np
+import pytest
+
+from paper_2010_04116_amd import binding, synth
+from parity import compare, make_inputs, run_both
+
+pytestmark = pytest.mark.gpu
+TINY = synth.WORKLOADS["tiny"]
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4])
+def test_tiny_fp32_window_sum(n):
+    w = TINY.with_(n=n)
+    say("case tiny fp32 n =", n)
+    got, ref = run_both(w)
+    say("worst", compare(w, got, ref, f"tiny n={n}"))
+
+
+@pytest.mark.parametrize("route", ["far_head", "mean_local_far"])
+@pytest.mark.parametrize("n", [1, 2, 3, 4])
+def test_tiny_fp32_paper_routes(n, route):
+    w = TINY.with_(n=n)
+    say("case tiny fp32 route", route, "n =", n)
+    got, ref = run_both(w, route=route)
+    say("worst", compare(w, got, ref, f"tiny {route} n={n}"))
+
+
+def test_fp32_two_blocks_many_components():
+    w = TINY.with_(K=6, L=2, n=3, B=3, T=16)
+    say("case fp32 K=6 L=2 n=3")
+    got, ref = run_both(w, seed=1)
+    say("worst", compare(w, got, ref, "K6L2"))
+    got, ref = run_both(w, seed=1, route="mean_local_far")
+    say("worst", compare(w, got, ref, "K6L2 mean"))
+
+
+def test_fp32_ragged_shapes():
+    """Sizes that are not multiples of any tile: d=48 (3 heads of 16), m=100, V=77, N=39."""
+    w = synth.Workload("ragged", "f32", K=3, L=1, d=48, H=3, m=100, V=77, B=3, T=13, n=2)
+    say("case ragged fp32")
+    got, ref = run_both(w, seed=2, head_chunk=16)     # 39 rows -> chunks 16,16,7
+    say("worst", compare(w, got, ref, "ragged"))
+
+
+def test_fp32_single_component_and_single_token():
+    w = synth.Workload("k1", "f32", K=1, L=1, d=32, H=2, m=64, V=16, B=2, T=1, n=1)
+    say("case K=1 T=1")
+    got, ref = run_both(w, seed=3)
+    say("worst", compare(w, got, ref, "K1T1"))
+
+
+def test_head_chunking_does_not_change_results():
+    w = TINY
+    params, x0, tgt = make_inputs(w)
+    a = binding.run_step(w, params, x0, tgt, head_chunk=64)
+    b = binding.run_step(w, params, x0, tgt, head_chunk=16)
+    np.testing.assert_allclose(a["losses"], b["losses"], rtol=1e-6)
+    for k in range(w.K):
+        np.testing.assert_allclose(a["head_grads"][k], b["head_grads"][k], rtol=1e-4, atol=1e-8)
+
+
+def test_step_is_bit_reproducible_and_restartable():
+    w = TINY
+    params, x0, tgt = make_inputs(w)
+    st = binding.Step(w, binding.pack_params(w, params))
+    st.set_inputs(x0, tgt)
+    st.run()
+    a = st.results()
+    st.run()                      # a second step on the same context: nothing accumulates
+    b = st.results()
+    st.close()
+    assert np.array_equal(a["losses"], b["losses"])
+    for k in range(w.K):
+        for name in synth.BLOCK_TENSORS:
+            assert np.array_equal(a["comp_grads"][k][0][name], b["comp_grads"][k][0][name]), name
+        assert np.array_equal(a["head_grads"][k], b["head_grads"][k])
+
+
+def test_call_order_errors_on_device():
+    w = TINY
+    params, x0, tgt = make_inputs(w)
+    st = binding.Step(w, binding.pack_params(w, params))
+    st.set_inputs(x0, tgt)
+    with pytest.raises(binding.InterlockError) as e:
+        binding.il_stage_backward_nwise(st.ctx, w.K)
+    assert e.value.status == binding.IL_E_STATE
+    for k in range(1, w.K + 1):
+        binding.il_stage_forward(st.ctx, k, st.x[k - 1], st.x[k])
+    with pytest.raises(binding.InterlockError) as e:   # head K not evaluated yet
+        binding.il_stage_backward_nwise(st.ctx, w.K)
+    assert e.value.status == binding.IL_E_STATE
+    st.close()
+
+
+# ---------------------------------------------------------------- bf16 -------------
+
+def test_bf16_reduced_small():
+    """Small's structure (K=4 x 2 blocks, head width 64) at a quarter of its width."""
+    w = synth.Workload("small_q", "bf16", K=4, L=2, d=256, H=4, m=1024, V=2048, B=2, T=128, n=2)
+    say("case bf16 reduced small")
+    got, ref = run_both(w, seed=4)
+    say("worst", compare(w, got, ref, "small_q"))
+
+
+@pytest.mark.parametrize("n", [1, 2])
+def test_small_bf16_full_step(n):
+    w = synth.WORKLOADS["small"].with_(n=n)
+    say("case small bf16 n =", n)
+    got, ref = run_both(w, seed=5, random_ln=False)
+    say("worst", compare(w, got, ref, f"small n={n}"))
+    assert np.all(np.abs(ref["losses"] - np.log(w.V)) < 0.5)     # uniform tokens: loss near ln V

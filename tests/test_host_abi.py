@@ -1,0 +1,101 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol the header declares, plans routes like the oracle, reports sizes, and turns
+misuse into status codes."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from oracle import interlock as O
+from paper_2010_04116_amd import binding, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = binding.load()
+    hdr = open(os.path.join(ROOT, "include", "interlock.h")).read()
+    declared = set(re.findall(r"\b(il_[a-z_]+)\s*\(", hdr))
+    assert {"il_init", "il_stage_forward", "il_head_xent", "il_stage_backward_nwise", "il_free"} <= declared
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert set(binding.SYMBOLS) == declared
+
+
+@pytest.mark.parametrize("route", O.ROUTES)
+def test_routing_plan_matches_oracle(route):
+    for K in range(1, 9):
+        for n in range(1, K + 1):
+            live, passes = binding.il_routing_plan(K, n, route)
+            plan = O.stream_plan(K, n, route)
+            assert passes == [len(plan[k]) for k in range(1, K + 1)], (K, n)
+            assert all(1 <= l <= p for l, p in zip(live, passes))
+            if route == "window_sum":
+                # streams that stop at component 1 (heads 1..n) travel as one
+                want = [len([j for j in plan[k] if j > n]) + (1 if k <= n else 0) for k in range(1, K + 1)]
+                assert live == want, (K, n)
+    with pytest.raises(binding.InterlockError):
+        binding.il_routing_plan(4, 5, route)
+    with pytest.raises(binding.InterlockError):
+        binding.il_routing_plan(4, 0, route)
+
+
+def test_size_query_and_param_count():
+    for name, w in synth.WORKLOADS.items():
+        cfg = binding.make_config(w)
+        pb, gb, wb = binding.query_sizes(cfg)
+        eb = 4 if w.dtype == "f32" else 2
+        assert pb == binding.param_count(w) * eb
+        assert gb == binding.param_count(w) * 4
+        assert wb > 0 and wb % 256 == 0
+    assert binding.param_count(synth.WORKLOADS["medium"]) == 24 * (12 * 1024 ** 2 + 13 * 1024) + 4 * 1024 * 32768
+
+
+def test_misuse_returns_status_codes():
+    lib = binding.load()
+    w = synth.WORKLOADS["tiny"]
+    ctx = C.c_void_p()
+    assert lib.il_init(None, C.byref(ctx)) == binding.IL_E_ARG
+    for field, val, want in [("n", 0, binding.IL_E_ARG), ("n", 5, binding.IL_E_ARG),
+                             ("dtype", 7, binding.IL_E_ARG), ("route", 9, binding.IL_E_ARG),
+                             ("n_heads", 3, binding.IL_E_SHAPE), ("d_model", 4096, binding.IL_E_SHAPE),
+                             ("K", 0, binding.IL_E_ARG)]:
+        cfg = binding.make_config(w)
+        setattr(cfg, field, val)
+        assert lib.il_init(C.byref(cfg), C.byref(ctx)) == want, field
+    cfg = binding.make_config(w.with_(dtype="bf16", B=1, T=33))
+    assert lib.il_init(C.byref(cfg), C.byref(ctx)) == binding.IL_E_SHAPE
+    # buffers too small
+    cfg = binding.make_config(w)
+    pb, gb, wb = binding.query_sizes(cfg)
+    cfg.params, cfg.grads, cfg.workspace = 4096, 4096, 4096
+    cfg.params_bytes, cfg.grads_bytes, cfg.workspace_bytes = pb, gb, wb - 1
+    assert lib.il_init(C.byref(cfg), C.byref(ctx)) == binding.IL_E_WORKSPACE
+    # a context over fake pointers: call-order errors are caught before any launch
+    cfg.workspace_bytes = wb
+    assert lib.il_init(C.byref(cfg), C.byref(ctx)) == binding.IL_OK
+    fake = C.c_void_p(4096)
+    fake2 = C.c_void_p(8192)
+    assert lib.il_stage_forward(ctx, 2, fake, fake2) == binding.IL_E_STATE
+    assert lib.il_stage_forward(ctx, 0, fake, fake2) == binding.IL_E_ARG
+    assert lib.il_stage_forward(ctx, 1, fake, fake) == binding.IL_E_ARG
+    assert lib.il_stage_forward(ctx, 1, None, fake2) == binding.IL_E_ARG
+    assert lib.il_head_xent(ctx, 1, fake, fake, fake) == binding.IL_E_STATE
+    assert lib.il_stage_backward_nwise(ctx, 4, None) == binding.IL_E_STATE
+    assert lib.il_stage_backward_nwise(ctx, 9, None) == binding.IL_E_ARG
+    assert lib.il_free(ctx) == binding.IL_OK
+    assert lib.il_free(None) == binding.IL_E_ARG
+    assert "IL_E_STATE" in binding.il_status_string(binding.IL_E_STATE)
+
+
+def test_pack_unpack_roundtrip():
+    import numpy as np
+    w = synth.WORKLOADS["tiny"]
+    p = synth.make_params(w, random_bias=True)
+    flat = binding.pack_params(w, p)
+    back = binding.unpack_grads(w, flat)
+    for k in range(w.K):
+        for name in synth.BLOCK_TENSORS:
+            assert np.array_equal(back["components"][k][0][name], p["components"][k][0][name])
+        assert np.array_equal(back["heads"][k], p["heads"][k])
