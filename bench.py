@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of one n-wise interlocking-backprop training step on one MI355X.
+
+A step is the whole hot path: K x (il_stage_forward + il_head_xent) and the n-wise
+truncated backward il_stage_backward_nwise for k = K..1, all parameter gradients final,
+on seeded synthetic tokens already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps 20] [--warmup 5] [--workload small] [--n N]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_F32_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def minimal_flops(w):
+    """Algorithmic flops of one step, not counting recomputation: per block forward
+    GEMMs 24 N d^2 (for m = 4d; general: 2N(4d^2 + 2dm)) and causal attention 2 B T^2 d;
+    backward per distinct stream: dgrad = forward GEMM flops, attention backward 2.5x;
+    one weight-gradient pass per block; head 3 x 2 N d V."""
+    from paper_2010_04116_amd import binding
+    N, d, m = w.N, w.d, w.m
+    G = 2.0 * N * (4 * d * d + 2 * d * m)
+    At = 2.0 * w.B * w.T * w.T * d
+    live, _ = binding.il_routing_plan(w.K, w.n, "window_sum")
+    tot = 0.0
+    for k in range(w.K):
+        tot += w.L * (G + At)                                   # forward
+        tot += w.L * ((live[k] + 1) * G + 2.5 * live[k] * At)   # dgrad per stream + one wgrad
+        tot += 3 * 2.0 * N * d * w.V                            # head fwd + dx + dW
+    return tot
+
+
+def time_steps(st, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        st.run()
+    st.stream.synchronize()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(st.stream)
+    for _ in range(steps):
+        st.run()
+    e1.record(st.stream)
+    st.stream.synchronize()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3
+    return e0.elapsed_time(e1) / steps, wall / steps
+
+
+def kernel_table(w, flat, steps):
+    """Per-kernel-class HIP-event times from the library's own profiling hooks."""
+    from paper_2010_04116_amd import binding
+    st = binding.Step(w, flat, profile=True)
+    st.set_inputs(*INPUTS)
+    st.run()
+    binding.il_profile_read(st.ctx)             # discard warm-up
+    for _ in range(steps):
+        st.run()
+    prof = binding.il_profile_read(st.ctx)
+    st.close()
+    for v in prof.values():
+        v["ms_per_step"] = v["ms"] / steps
+        v["flops_per_step"] = v["flops"] / steps
+        v["bytes_per_step"] = v["bytes"] / steps
+        v["launches_per_step"] = v["launches"] / steps
+    return prof
+
+
+def cpu_baseline(w, params, x0, tgt):
+    """The float64 oracle, as it stands, on the host cores, on a bounded sample: the
+    first `b` sequences of the batch through the whole model (every per-token cost is
+    the same as in the full batch, so tokens/s is directly comparable)."""
+    from oracle import interlock as O
+    # aim at ~10-30 s: assume ~100 GFLOP/s float64 on the host
+    full = minimal_flops(w)
+    b = int(max(1, min(w.B, np.floor(w.B * 2.0e12 / full))))
+    ws = w.with_(B=b)
+    xs = x0[: b * w.T]
+    ts = tgt[:b]
+    t0 = time.perf_counter()
+    O.nwise_streams(params, xs, ts, ws.B, ws.T, ws.H, ws.n)
+    dt = time.perf_counter() - t0
+    return {"value": b * w.T / dt, "unit": "tokens/s", "cores": len(os.sched_getaffinity(0)),
+            "kind": "oracle", "seconds": dt,
+            "sample": f"first {b} of {w.B} sequences ({b * w.T} tokens), all {w.K} components and heads, "
+                      f"n={w.n}, float64 numpy stream path, one run"}
+
+
+INPUTS = None
+
+
+def main():
+    global INPUTS
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="small")
+    ap.add_argument("--n", type=int, default=0, help="override the workload's window")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); depthwise sharding "
+                 "across GPUs is described in DESIGN.md and not built")
+    if int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: launched with WORLD_SIZE > 1; this build runs on exactly one GPU")
+
+    import torch
+    from paper_2010_04116_amd import binding, synth
+    w = synth.WORKLOADS[a.workload]
+    if a.n:
+        w = w.with_(n=a.n)
+    params = synth.make_params(w)                      # N(0,0.02) weights, biases 0, LN 1/0
+    inp, tgt = synth.make_tokens(w)
+    x0 = synth.make_x0(w, inp)
+    flat = binding.pack_params(w, params)
+    INPUTS = (x0, tgt)
+
+    st = binding.Step(w, flat)
+    st.set_inputs(x0, tgt)
+    ms, wall_ms = time_steps(st, a.steps, a.warmup)
+    losses = st.results()["losses"]
+    st.close()
+    assert np.all(np.isfinite(losses)) and np.all(np.abs(losses - np.log(w.V)) < 1.0), losses
+
+    prof = kernel_table(w, flat, max(2, min(a.steps, 5)))
+    flops = minimal_flops(w)
+    tokens_per_s = w.N / (ms * 1e-3)
+    gemm = [k for k in prof if k.startswith("gemm")]
+    g_ms = sum(prof[k]["ms_per_step"] for k in gemm)
+    g_fl = sum(prof[k]["flops_per_step"] for k in gemm)
+    g_n = sum(prof[k]["launches_per_step"] for k in gemm)
+    peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_F32_TFLOPS
+    achieved = g_fl / (g_ms * 1e-3) / 1e12 if g_ms > 0 else 0.0
+    out = {
+        "metric": "tokens/sec per n-wise train step at 1 GPU",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}_{w.dtype}_n{w.n}", "K": w.K, "blocks_per_component": w.L,
+                   "d_model": w.d, "n_heads": w.H, "d_mlp": w.m, "vocab": w.V, "batch": w.B, "seq": w.T,
+                   "n": w.n, "route": "window_sum", "param_seed": synth.PARAM_SEED,
+                   "token_seed": synth.TOKEN_SEED},
+        "mfma_utilisation_pct_of_bf16_peak": 100.0 * flops / (ms * 1e-3) / (PEAK_BF16_TFLOPS * 1e12),
+        "algorithmic_tflop_per_step": flops / 1e12,
+        "wall_ms_per_step": wall_ms,
+        "roofline": {"bound": "mfma", "kernel": "gemm (forward, dgrad, wgrad, head) launches of one step",
+                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                     "traffic": None, "launches_per_step": g_n, "avg_launch_ms": g_ms / max(g_n, 1)},
+        "kernels": {k: {"ms_per_step": round(v["ms_per_step"], 4), "launches": v["launches_per_step"],
+                        "tflops": (v["flops_per_step"] / (v["ms_per_step"] * 1e-3) / 1e12)
+                        if v["ms_per_step"] > 0 and v["flops_per_step"] else None,
+                        "gbs": (v["bytes_per_step"] / (v["ms_per_step"] * 1e-3) / 1e9)
+                        if v["ms_per_step"] > 0 and v["bytes_per_step"] else None}
+                    for k, v in prof.items()},
+        "losses": [float(x) for x in losses],
+    }
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, params, x0.astype(np.float64), tgt)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -553,7 +553,7 @@ int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets,
   }
   {
     Scope sc(c, KC_MISC, 0, (double)N * 4);
-    IL_TRY(sum_scalar(c->rowloss, N, 1.f, loss_out, c->stream));
+    IL_TRY(sum_scalar(c->rowloss, N, 1.f / N, loss_out, c->stream));
   }
   c->head_done[k] = 1;
   return IL_OK;
