@@ -121,6 +121,5 @@ hipError_t gemm_simt(int dtype, const GemmArgs &g, hipStream_t s) {
 }
 
 hipError_t gemm_f32(const GemmArgs &g, hipStream_t s) { return gemm_simt(0, g, s); }
-hipError_t gemm_bf16(const GemmArgs &g, hipStream_t s) { return gemm_simt(1, g, s); }  // bring-up
 
 }  // namespace il

@@ -117,3 +117,30 @@ def test_small_bf16_full_step(n):
     got, ref = run_both(w, seed=5, random_ln=False)
     say("worst", compare(w, got, ref, f"small n={n}"))
     assert np.all(np.abs(ref["losses"] - np.log(w.V)) < 0.5)     # uniform tokens: loss near ln V
+
+
+# ------------------------------------------------ real-shape slices (bf16) ---------
+
+def test_medium_shape_one_component_and_head():
+    """One block + head at Medium's real shape (N=4096, d=1024, m=4096, V=32768): the
+    GEMM tile configurations and head chunking the benchmark uses."""
+    w = synth.WORKLOADS["medium"].with_(K=1, L=1, n=1)
+    say("case medium slice K=1 L=1")
+    got, ref = run_both(w, seed=6, random_ln=False)
+    say("worst", compare(w, got, ref, "medium slice"))
+
+
+def test_medium_shape_stacked_streams():
+    """Two live gradient streams through real-shape blocks (K=3, n=2; smaller vocab)."""
+    w = synth.WORKLOADS["medium"].with_(K=3, L=1, n=2, V=8192)
+    say("case medium stacked K=3 n=2")
+    got, ref = run_both(w, seed=7, random_ln=False)
+    say("worst", compare(w, got, ref, "medium stacked"))
+
+
+def test_large_shape_one_component_and_head():
+    """One block + head at Large's real shape (d=2048, head width 128, V=50304 = 393*128)."""
+    w = synth.WORKLOADS["large"].with_(K=1, L=1, n=1)
+    say("case large slice K=1 L=1")
+    got, ref = run_both(w, seed=8, random_ln=False)
+    say("worst", compare(w, got, ref, "large slice"))
