@@ -134,7 +134,8 @@ def main():
     ms, wall_ms = time_steps(st, a.steps, a.warmup)
     losses = st.results()["losses"]
     st.close()
-    assert np.all(np.isfinite(losses)) and np.all(np.abs(losses - np.log(w.V)) < 1.0), losses
+    # uniform random tokens: every loss sits at ln V plus half the logit variance, which grows with depth
+    assert np.all(np.isfinite(losses)) and np.all(losses > np.log(w.V) - 0.5) and np.all(losses < np.log(w.V) + 4), losses
 
     prof = kernel_table(w, flat, max(2, min(a.steps, 5)))
     flops = minimal_flops(w)

@@ -170,10 +170,14 @@ hipError_t attention_backward_simt(int dtype, const void *qkv, const void *o, co
 #undef B16
 }
 
-// Front ends used by the step: every (dtype, head width) goes to the kernels above
-// until a matrix-core kernel covers it.
+hipError_t attention_forward_mfma(const void *qkv, int B, int T, int H, int dh, void *o, float *lse,
+                                  hipStream_t s);
+
+// Front ends used by the step: bf16 with head width 64 or 128 runs on the matrix cores,
+// everything else (fp32; bf16 with head width 16 or 32) on the kernels above.
 hipError_t attention_forward(int dtype, const void *qkv, int B, int T, int H, int dh, void *o, float *lse,
                              hipStream_t s) {
+  if (dtype == 1 && (dh == 64 || dh == 128)) return attention_forward_mfma(qkv, B, T, H, dh, o, lse, s);
   return attention_forward_simt(dtype, qkv, B, T, H, dh, o, lse, s);
 }
 hipError_t attention_backward(int dtype, const void *qkv, const void *o, const void *d_o, const float *lse,
