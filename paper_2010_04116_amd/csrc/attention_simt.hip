@@ -173,6 +173,9 @@ hipError_t attention_backward_simt(int dtype, const void *qkv, const void *o, co
 hipError_t attention_forward_mfma(const void *qkv, int B, int T, int H, int dh, void *o, float *lse,
                                   hipStream_t s);
 
+hipError_t attention_backward_mfma(const void *qkv, const void *o, const void *d_o, const float *lse, int ns,
+                                   int B, int T, int H, int dh, void *dqkv, float *dsum, hipStream_t s);
+
 // Front ends used by the step: bf16 with head width 64 or 128 runs on the matrix cores,
 // everything else (fp32; bf16 with head width 16 or 32) on the kernels above.
 hipError_t attention_forward(int dtype, const void *qkv, int B, int T, int H, int dh, void *o, float *lse,
@@ -182,6 +185,8 @@ hipError_t attention_forward(int dtype, const void *qkv, int B, int T, int H, in
 }
 hipError_t attention_backward(int dtype, const void *qkv, const void *o, const void *d_o, const float *lse,
                               int ns, int B, int T, int H, int dh, void *dqkv, float *dsum, hipStream_t s) {
+  if (dtype == 1 && (dh == 64 || dh == 128))
+    return attention_backward_mfma(qkv, o, d_o, lse, ns, B, T, H, dh, dqkv, dsum, s);
   return attention_backward_simt(dtype, qkv, o, d_o, lse, ns, B, T, H, dh, dqkv, dsum, s);
 }
 
