@@ -84,6 +84,7 @@ struct GemmArgs {
   const void *aux;    // T, EPI_GELU_BWD
   int aux_wrap;       // rows of aux (row index taken modulo this)
   float scale;        // EPI_WGRAD
+  uint32_t a_bytes, b_bytes;  // operand extents in bytes (filled by the bf16 front end)
   int beta;           // EPI_WGRAD: accumulate into C
 };
 

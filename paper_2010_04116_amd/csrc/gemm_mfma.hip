@@ -14,12 +14,17 @@
 // registers and writes eight 16-byte k-vectors, so the MFMA operand fetch from LDS is one
 // ds_read_b128 per 32x16 fragment in every case.
 //
+// Loads.  Operands are read through raw buffer descriptors sized to the operand, so rows or
+// k beyond the edge read as zero without a branch.
+//
 // LDS swizzle.  The 16-byte chunk c of row r lives at chunk c ^ ((r ^ (r >> 3)) & 7): eight
 // consecutive rows (operand fetch, k-contiguous fill) and eight rows 8 apart (transposing
 // fill) both spread over all eight chunk positions, so neither side bank-conflicts.
 //
 // The grid is one-dimensional; tile ids are regrouped so that the workgroups that land on
 // one XCD (id mod 8) work on neighbouring tiles and share their operands in that XCD's L2.
+#include <algorithm>
+
 #include "common.h"
 
 namespace il {
@@ -27,25 +32,30 @@ namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
 
 constexpr int BK = 64;           // K step, bf16 elements
 constexpr int ROWB = BK * 2;     // bytes per LDS row
+constexpr uint32_t kOob = 0x80000000u;  // byte offset beyond every operand: the buffer load returns 0
 
 __device__ inline int swz(int row, int chunk) { return row * ROWB + ((chunk ^ ((row ^ (row >> 3)) & 7)) << 4); }
 
-__device__ inline uint4 ldg16(const bf16_t *p) { return *reinterpret_cast<const uint4 *>(p); }
+// Raw buffer descriptor over [base, base+bytes): loads past the end return zero, so tile
+// edges need no branches (the range check covers the VGPR offset; the scalar offset is
+// kept at zero because it is not part of the check).
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
+}
 
 // 8x8 transpose of 16-bit elements: in[r] holds row r (8 elements), out[c] column c.
-__device__ inline void transpose8x8(const uint4 (&in)[8], uint4 (&out)[8]) {
-  const uint32_t *s = reinterpret_cast<const uint32_t *>(in);   // s[r*4 + w]
-  uint32_t *o = reinterpret_cast<uint32_t *>(out);              // o[c*4 + w]
+__device__ inline void transpose8x8(const u32x4 (&in)[8], u32x4 (&out)[8]) {
 #pragma unroll
   for (int w = 0; w < 4; ++w)      // source dword = columns 2w, 2w+1
 #pragma unroll
     for (int p = 0; p < 4; ++p) {  // row pair 2p, 2p+1 -> destination dword p
-      uint32_t a = s[(2 * p) * 4 + w], b = s[(2 * p + 1) * 4 + w];
-      o[(2 * w) * 4 + p] = (a & 0xFFFFu) | (b << 16);
-      o[(2 * w + 1) * 4 + p] = (a >> 16) | (b & 0xFFFF0000u);
+      const uint32_t a = in[2 * p][w], b = in[2 * p + 1][w];
+      out[2 * w][p] = (a & 0xFFFFu) | (b << 16);
+      out[2 * w + 1][p] = (a >> 16) | (b & 0xFFFF0000u);
     }
 }
 
@@ -53,27 +63,37 @@ __device__ inline void transpose8x8(const uint4 (&in)[8], uint4 (&out)[8]) {
 template <int ROWS, bool KMAJOR>
 struct TileLoader {
   static constexpr int NCH = KMAJOR ? 8 : ROWS / 32;  // 16-byte registers per thread
-  uint4 r[NCH];
+  u32x4 r[NCH];
+  uint32_t voff[NCH];  // byte offset of each load at k = 0 (kOob where the row is outside the operand)
+  int kofs;            // this thread's k offset inside the 64-wide step (first of its loads)
+  uint32_t kstride;    // bytes per unit of k
 
-  // base: operand origin; row0: first tile row; rows: operand rows (bound);
-  // k0: first k of this step in operand coordinates; kend: bound on k; ld: leading dimension
-  __device__ inline void fetch(const bf16_t *base, int row0, int rows, long k0, long kend, int ld, int t) {
+  __device__ inline void init(int row0, int rows, int ld, int t) {
     if constexpr (!KMAJOR) {
+      kofs = (t & 7) * 8;
+      kstride = 2;
 #pragma unroll
       for (int i = 0; i < NCH; ++i) {
-        const int c = t + 256 * i, row = c >> 3, kc = c & 7;
-        const long k = k0 + kc * 8;
-        r[i] = (row0 + row < rows && k < kend) ? ldg16(base + (size_t)(row0 + row) * ld + k)
-                                                : make_uint4(0, 0, 0, 0);
+        const int row = row0 + ((t + 256 * i) >> 3);
+        voff[i] = row < rows ? ((uint32_t)row * ld + kofs) * 2u : kOob;
       }
     } else {
       const int mb = t % (ROWS / 8), kb = t / (ROWS / 8);
       const bool on = (ROWS >= 256 || t < ROWS) && (row0 + mb * 8 < rows);
+      kofs = kb * 8;
+      kstride = (uint32_t)ld * 2u;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const long k = k0 + kb * 8 + i;
-        r[i] = (on && k < kend) ? ldg16(base + (size_t)k * ld + row0 + mb * 8) : make_uint4(0, 0, 0, 0);
-      }
+      for (int i = 0; i < 8; ++i) voff[i] = on ? ((uint32_t)(kofs + i) * ld + row0 + mb * 8) * 2u : kOob;
+    }
+  }
+
+  // k0: first k of this step in operand coordinates; kend: bound on k
+  __device__ inline void fetch(__amdgpu_buffer_rsrc_t rs, int k0, int kend) {
+    const uint32_t adv = (uint32_t)k0 * kstride;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const bool ok = k0 + kofs + (KMAJOR ? i : 0) < kend;
+      r[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, ok ? voff[i] + adv : kOob, 0, 0);
     }
   }
 
@@ -81,26 +101,42 @@ struct TileLoader {
     if constexpr (!KMAJOR) {
 #pragma unroll
       for (int i = 0; i < NCH; ++i) {
-        const int c = t + 256 * i, row = c >> 3, kc = c & 7;
-        *reinterpret_cast<uint4 *>(lds + swz(row, kc)) = r[i];
+        const int c = t + 256 * i;
+        *reinterpret_cast<u32x4 *>(lds + swz(c >> 3, c & 7)) = r[i];
       }
     } else {
       if (ROWS >= 256 || t < ROWS) {
         const int mb = t % (ROWS / 8), kb = t / (ROWS / 8);
-        uint4 o[8];
+        u32x4 o[8];
         transpose8x8(r, o);
 #pragma unroll
-        for (int c = 0; c < 8; ++c) *reinterpret_cast<uint4 *>(lds + swz(mb * 8 + c, kb)) = o[c];
+        for (int c = 0; c < 8; ++c) *reinterpret_cast<u32x4 *>(lds + swz(mb * 8 + c, kb)) = o[c];
       }
     }
   }
 };
+
+__device__ inline void unpack8(const u32x4 v, float (&f)[8]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    f[2 * i] = bf16_to_f32((bf16_t)(v[i] & 0xFFFFu));
+    f[2 * i + 1] = bf16_to_f32((bf16_t)(v[i] >> 16));
+  }
+}
+__device__ inline u32x4 pack8(const float (&f)[8]) {
+  u32x4 v;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) v[i] = (uint32_t)f32_to_bf16(f[2 * i]) | ((uint32_t)f32_to_bf16(f[2 * i + 1]) << 16);
+  return v;
+}
 
 template <int BM, int BN, bool AKM, bool BKM, int EPI>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   constexpr int WTM = BM / 2, WTN = BN / 2;   // wavefront tile
   constexpr int MI = WTM / 32, NI = WTN / 32; // MFMA tiles per wavefront
   constexpr int STAGE = (BM + BN) * ROWB;
+  constexpr int SP = WTN + 4;                 // epilogue staging row pitch, floats
+  static_assert(4 * 32 * SP * 4 <= 2 * STAGE, "epilogue staging must fit in the operand buffers");
   __shared__ __attribute__((aligned(16))) char smem[2 * STAGE];
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -118,22 +154,23 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   const int tm = first_m + (pid % per_group) % gsize, tn = (pid % per_group) / gsize;
   const int m0 = tm * BM, n0 = tn * BN;
 
-  const bf16_t *A = (const bf16_t *)g.A;
-  const bf16_t *B = (const bf16_t *)g.B;
+  const __amdgpu_buffer_rsrc_t ra = make_rsrc(g.A, g.a_bytes), rb = make_rsrc(g.B, g.b_bytes);
   TileLoader<BM, AKM> la;
   TileLoader<BN, BKM> lb;
+  la.init(m0, g.M, g.lda, t);
+  lb.init(n0, g.N, g.ldb, t);
   const int nk = (g.K + BK - 1) / BK;
   const bool seg = AKM && BKM && g.segs.nseg > 0;
 
   auto fetch = [&](int kt) {
-    long ka = (long)kt * BK, kb = ka, kenda = g.K, kendb = g.K;
+    int ka = kt * BK, kb = ka, kenda = g.K, kendb = g.K;
     if (seg) {  // segmented reduction: a K step never straddles two segments
-      const int s = (int)(ka / g.seg_len), r = (int)(ka % g.seg_len);
+      const int s = ka / g.seg_len, r = ka % g.seg_len;
       ka = r; kenda = g.seg_len;
       kb = g.segs.row0[s] + r; kendb = g.segs.row0[s] + g.seg_len;
     }
-    la.fetch(A, m0, g.M, ka, kenda, g.lda, t);
-    lb.fetch(B, n0, g.N, kb, kendb, g.ldb, t);
+    la.fetch(ra, ka, kenda);
+    lb.fetch(rb, kb, kendb);
   };
 
   floatx16 acc[MI][NI];
@@ -154,20 +191,30 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
     const char *sa = smem + (kt & 1) * STAGE;
     const char *sb = sa + BM * ROWB;
     if (kt + 1 < nk) fetch(kt + 1);
+    // operand fragments are fetched from LDS one 16-wide k slice ahead of the MFMAs that use them
+    bf16x8 af[2][MI], bfr[2][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+      af[0][i] = *reinterpret_cast<const bf16x8 *>(sa + swz(wm * WTM + i * 32 + frow, fchunk));
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+      bfr[0][j] = *reinterpret_cast<const bf16x8 *>(sb + swz(wn * WTN + j * 32 + frow, fchunk));
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 af[MI], bfr[NI];
+      const int cur = ks & 1, nxt = cur ^ 1;
+      if (ks + 1 < BK / 16) {
 #pragma unroll
-      for (int i = 0; i < MI; ++i)
-        af[i] = *reinterpret_cast<const bf16x8 *>(sa + swz(wm * WTM + i * 32 + frow, 2 * ks + fchunk));
+        for (int i = 0; i < MI; ++i)
+          af[nxt][i] = *reinterpret_cast<const bf16x8 *>(sa + swz(wm * WTM + i * 32 + frow, 2 * (ks + 1) + fchunk));
 #pragma unroll
-      for (int j = 0; j < NI; ++j)
-        bfr[j] = *reinterpret_cast<const bf16x8 *>(sb + swz(wn * WTN + j * 32 + frow, 2 * ks + fchunk));
+        for (int j = 0; j < NI; ++j)
+          bfr[nxt][j] = *reinterpret_cast<const bf16x8 *>(sb + swz(wn * WTN + j * 32 + frow, 2 * (ks + 1) + fchunk));
+      }
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
         for (int j = 0; j < NI; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
     }
     if (kt + 1 < nk) {
       char *na = smem + ((kt + 1) & 1) * STAGE;
@@ -177,43 +224,80 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
     __syncthreads();
   }
 
-  // ---- epilogue: lane holds column (lane & 31), rows 8*(r/4) + 4*(lane>>5) + (r&3) of each tile ----
-  const bf16_t *bias = (const bf16_t *)g.bias;
+  // ---- epilogue.  A lane holds column (lane & 31) and rows 8*(r/4) + 4*(lane>>5) + (r&3) of
+  // each 32x32 tile; each wavefront passes one 32-row strip at a time through its own LDS
+  // region so that every lane ends up with 8 consecutive columns of one row: 16-byte bf16 /
+  // 32-byte fp32 stores and equally wide reads of bias, residual and pre-activation.
+  float *stg = reinterpret_cast<float *>(smem) + wave * (32 * SP);
+  constexpr int LPR = WTN / 8, RPP = 64 / LPR, PASSES = 32 / RPP;
+  const int hh = lane >> 5, lq = lane & 31;
+  const int col_l = (lane % LPR) * 8, row_in = lane / LPR;
+  const int gcol = n0 + wn * WTN + col_l;
+  float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_RES) {
+    if (gcol < g.N) unpack8(*reinterpret_cast<const u32x4 *>((const bf16_t *)g.bias + gcol), bv);
+  }
 #pragma unroll
-  for (int j = 0; j < NI; ++j) {
-    const int col = n0 + wn * WTN + j * 32 + (lane & 31);
-    if (col >= g.N) continue;
-    float bv = 0.f;
-    if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_RES) bv = bf16_to_f32(bias[col]);
+  for (int i = 0; i < MI; ++i) {
 #pragma unroll
-    for (int i = 0; i < MI; ++i) {
+    for (int j = 0; j < NI; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = m0 + wm * WTM + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (row >= g.M) continue;
-        const size_t o = (size_t)row * g.ldc + col;
-        float v = acc[i][j][r];
-        if constexpr (EPI == EPI_STORE) {
-          ((bf16_t *)g.C)[o] = f32_to_bf16(v);
-        } else if constexpr (EPI == EPI_BIAS) {
-          ((bf16_t *)g.C)[o] = f32_to_bf16(v + bv);
-        } else if constexpr (EPI == EPI_BIAS_GELU) {
-          const bf16_t u = f32_to_bf16(v + bv);
-          ((bf16_t *)g.C)[o] = u;
-          ((bf16_t *)g.C2)[o] = f32_to_bf16(gelu_f(bf16_to_f32(u)));
-        } else if constexpr (EPI == EPI_BIAS_RES) {
-          ((float *)g.C)[o] = v + bv + g.res[o];
-        } else if constexpr (EPI == EPI_GELU_BWD) {
-          const float u = bf16_to_f32(((const bf16_t *)g.aux)[(size_t)(row % g.aux_wrap) * g.ldc + col]);
-          ((bf16_t *)g.C)[o] = f32_to_bf16(v * gelu_grad_f(u));
-        } else if constexpr (EPI == EPI_STORE_F32) {
-          ((float *)g.C)[o] = v;
-        } else {  // EPI_WGRAD
-          float *c = (float *)g.C + o;
-          *c = g.scale * v + (g.beta ? *c : 0.f);
+      for (int r = 0; r < 16; ++r) stg[(8 * (r >> 2) + 4 * hh + (r & 3)) * SP + j * 32 + lq] = acc[i][j][r];
+    __syncthreads();
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+      const int row_l = p * RPP + row_in;
+      const int grow = m0 + wm * WTM + i * 32 + row_l;
+      const float4 v0 = *reinterpret_cast<const float4 *>(stg + row_l * SP + col_l);
+      const float4 v1 = *reinterpret_cast<const float4 *>(stg + row_l * SP + col_l + 4);
+      if (grow >= g.M || gcol >= g.N) continue;
+      float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+      const size_t o = (size_t)grow * g.ldc + gcol;
+      if constexpr (EPI == EPI_STORE) {
+        *reinterpret_cast<u32x4 *>((bf16_t *)g.C + o) = pack8(v);
+      } else if constexpr (EPI == EPI_BIAS) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] += bv[e];
+        *reinterpret_cast<u32x4 *>((bf16_t *)g.C + o) = pack8(v);
+      } else if constexpr (EPI == EPI_BIAS_GELU) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] += bv[e];
+        const u32x4 u = pack8(v);
+        *reinterpret_cast<u32x4 *>((bf16_t *)g.C + o) = u;
+        unpack8(u, v);  // the activation is taken of the stored (rounded) pre-activation
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
+        *reinterpret_cast<u32x4 *>((bf16_t *)g.C2 + o) = pack8(v);
+      } else if constexpr (EPI == EPI_BIAS_RES) {
+        const float4 r0 = *reinterpret_cast<const float4 *>(g.res + o);
+        const float4 r1 = *reinterpret_cast<const float4 *>(g.res + o + 4);
+        float4 o0 = {v[0] + bv[0] + r0.x, v[1] + bv[1] + r0.y, v[2] + bv[2] + r0.z, v[3] + bv[3] + r0.w};
+        float4 o1 = {v[4] + bv[4] + r1.x, v[5] + bv[5] + r1.y, v[6] + bv[6] + r1.z, v[7] + bv[7] + r1.w};
+        *reinterpret_cast<float4 *>((float *)g.C + o) = o0;
+        *reinterpret_cast<float4 *>((float *)g.C + o + 4) = o1;
+      } else if constexpr (EPI == EPI_GELU_BWD) {
+        float u[8];
+        unpack8(*reinterpret_cast<const u32x4 *>((const bf16_t *)g.aux + (size_t)(grow % g.aux_wrap) * g.ldc + gcol), u);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(u[e]);
+        *reinterpret_cast<u32x4 *>((bf16_t *)g.C + o) = pack8(v);
+      } else if constexpr (EPI == EPI_STORE_F32) {
+        *reinterpret_cast<float4 *>((float *)g.C + o) = v0;
+        *reinterpret_cast<float4 *>((float *)g.C + o + 4) = v1;
+      } else {  // EPI_WGRAD
+        float *c = (float *)g.C + o;
+        float4 o0 = {g.scale * v[0], g.scale * v[1], g.scale * v[2], g.scale * v[3]};
+        float4 o1 = {g.scale * v[4], g.scale * v[5], g.scale * v[6], g.scale * v[7]};
+        if (g.beta) {
+          const float4 c0 = *reinterpret_cast<const float4 *>(c), c1 = *reinterpret_cast<const float4 *>(c + 4);
+          o0.x += c0.x; o0.y += c0.y; o0.z += c0.z; o0.w += c0.w;
+          o1.x += c1.x; o1.y += c1.y; o1.z += c1.z; o1.w += c1.w;
         }
+        *reinterpret_cast<float4 *>(c) = o0;
+        *reinterpret_cast<float4 *>(c + 4) = o1;
       }
     }
+    __syncthreads();
   }
 }
 
@@ -236,8 +320,22 @@ hipError_t pick_tile(const GemmArgs &g, hipStream_t s) {
 
 // The step uses exactly these (layout, epilogue) combinations; anything else is a
 // programming error in the caller and is reported instead of silently taking another path.
-hipError_t gemm_bf16(const GemmArgs &g, hipStream_t s) {
+hipError_t gemm_bf16(const GemmArgs &g0, hipStream_t s) {
+  GemmArgs g = g0;
   if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
+  if ((g.N & 7) || (g.ldc & 7) || ((uintptr_t)g.C & 15)) return hipErrorInvalidValue;
+  {  // operand extents for the buffer descriptors (bytes, below 2 GiB)
+    size_t arows = g.a_kmajor ? (size_t)(g.segs.nseg > 0 ? g.seg_len : g.K) : (size_t)g.M;
+    size_t brows = g.b_kmajor ? (size_t)g.K : (size_t)g.N;
+    if (g.b_kmajor && g.segs.nseg > 0) {
+      brows = 0;
+      for (int i = 0; i < g.segs.nseg; ++i) brows = std::max(brows, (size_t)g.segs.row0[i] + g.seg_len);
+    }
+    const size_t ab = arows * g.lda * 2, bb = brows * g.ldb * 2;
+    if (ab >= 0x7FFFFFFFull || bb >= 0x7FFFFFFFull) return hipErrorInvalidValue;
+    g.a_bytes = (uint32_t)ab;
+    g.b_bytes = (uint32_t)bb;
+  }
   if ((g.lda & 7) || (g.ldb & 7) || ((uintptr_t)g.A & 15) || ((uintptr_t)g.B & 15)) return hipErrorInvalidValue;
   if (g.a_kmajor && (g.M & 7)) return hipErrorInvalidValue;
   if (g.b_kmajor && (g.N & 7)) return hipErrorInvalidValue;
