@@ -162,6 +162,24 @@ int il_routing_plan(int32_t K, int32_t n, int32_t route, int32_t *live, int32_t 
 int il_profile_read(il_ctx *ctx, int32_t cap, const char **names, int64_t *launches, double *ms,
                     double *flops, double *bytes);
 
+/*
+ * Kernel-level test hook: one GEMM launch of the library's own kernels, outside any step, so
+ * that tests and micro-benchmarks can reach each tile configuration and epilogue directly.
+ *   C[M,N] = epilogue( sum_k A(m,k) B(k,n) )
+ * dtype: il_dtype of A, B (and of C for the bf16/fp32-typed epilogues, see `epi`);
+ * a_kmajor / b_kmajor: 0 = operand stored [rows, K] row-major, 1 = stored [K, rows] row-major;
+ * epi: 0 store (T) | 1 +bias (T) | 2 +bias, C = pre-activation, C2 = GELU (T, T) |
+ *      3 +bias +res (fp32 out) | 4 * GELU'(aux[row % aux_wrap]) (T) | 5 store fp32 |
+ *      6 C = scale*acc (+ C if beta) (fp32);
+ * tile: 0 = library's choice, else 1 = 256x256 / 4 wavefronts, 2 = 256x256 / 8 wavefronts,
+ *       3 = 128x128 / 4 wavefronts (bf16 only).
+ * All pointers are device pointers; unused ones may be NULL.  Returns an il_status.
+ */
+int il_test_gemm(int32_t dtype, const void *A, const void *B, int32_t M, int32_t N, int32_t K, int32_t lda,
+                 int32_t ldb, int32_t a_kmajor, int32_t b_kmajor, int32_t epi, void *C, void *C2, int32_t ldc,
+                 const void *bias, const float *res, const void *aux, int32_t aux_wrap, float scale,
+                 int32_t beta, int32_t tile, void *stream);
+
 /* Static string for a status code. */
 const char *il_status_string(int status);
 

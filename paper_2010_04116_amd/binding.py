@@ -22,7 +22,7 @@ IL_OK, IL_E_ARG, IL_E_SHAPE, IL_E_STATE, IL_E_WORKSPACE, IL_E_HIP = 0, -1, -2, -
 IL_F32, IL_BF16 = 0, 1
 ROUTES = {"window_sum": 0, "far_head": 1, "mean_local_far": 2}
 SYMBOLS = ("il_init", "il_stage_forward", "il_head_xent", "il_stage_backward_nwise", "il_free",
-           "il_routing_plan", "il_profile_read", "il_status_string")
+           "il_routing_plan", "il_profile_read", "il_status_string", "il_test_gemm")
 
 
 class il_config(C.Structure):
@@ -59,6 +59,8 @@ def load():
     lib.il_routing_plan.argtypes = [i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
     lib.il_profile_read.argtypes = [vp, i32, C.POINTER(C.c_char_p), C.POINTER(C.c_int64),
                                     C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.il_test_gemm.argtypes = [i32, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, i32, vp, vp, vp,
+                                 i32, C.c_float, i32, i32, vp]
     lib.il_status_string.argtypes = [C.c_int]
     lib.il_status_string.restype = C.c_char_p
     for name in SYMBOLS:
@@ -137,6 +139,16 @@ def il_stage_backward_nwise(ctx, k: int, dx0_out=None):
 
 def il_free(ctx):
     _check(load().il_free(ctx), "il_free")
+
+
+def il_test_gemm(dtype, A, B, M, N, K, lda, ldb, a_kmajor, b_kmajor, epi, Cout, C2=None, ldc=None, bias=None,
+                 res=None, aux=None, aux_wrap=1, scale=1.0, beta=0, tile=0, stream=None):
+    """One GEMM launch of the library's kernels on torch device tensors (test hook)."""
+    p = lambda t: t.data_ptr() if t is not None else None
+    rc = load().il_test_gemm(dtype, p(A), p(B), M, N, K, lda, ldb, a_kmajor, b_kmajor, epi, p(Cout), p(C2),
+                             ldc if ldc is not None else N, p(bias), p(res), p(aux), aux_wrap, scale, beta,
+                             tile, stream)
+    _check(rc, "il_test_gemm")
 
 
 def il_profile_read(ctx) -> Dict[str, dict]:

@@ -85,6 +85,7 @@ struct GemmArgs {
   int aux_wrap;       // rows of aux (row index taken modulo this)
   float scale;        // EPI_WGRAD
   uint32_t a_bytes, b_bytes;  // operand extents in bytes (filled by the bf16 front end)
+  int tile;           // bf16: 0 = choose by shape, 1 = 256x256/4 waves, 2 = 256x256/8 waves, 3 = 128x128
   int beta;           // EPI_WGRAD: accumulate into C
 };
 

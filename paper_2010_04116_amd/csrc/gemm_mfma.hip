@@ -1,9 +1,9 @@
 // bf16 GEMM on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulate,
 // with the library's fused epilogues.
 //
-// Tiling.  A 256-thread workgroup (4 wavefronts in a 2x2 arrangement) owns a BM x BN tile
-// of C and walks K in steps of 64.  Each wavefront owns (BM/2) x (BN/2) = MI x NI MFMA
-// tiles of 32x32, all held in accumulator registers.  Both operand tiles are staged in LDS
+// Tiling.  A workgroup of WGM x WGN wavefronts owns a BM x BN tile of C and walks K in steps
+// of 64.  Each wavefront owns (BM/WGM) x (BN/WGN) = MI x NI MFMA tiles of 32x32, all held in
+// accumulator registers.  Instantiated: 256x256 with 4 or 8 wavefronts, 128x128 with 4.  Both operand tiles are staged in LDS
 // as [row][64 k] bf16 with k contiguous (128 B per row), double buffered; the next K step
 // is fetched from HBM into registers while the current one is multiplied.
 //
@@ -59,14 +59,19 @@ __device__ inline void transpose8x8(const u32x4 (&in)[8], u32x4 (&out)[8]) {
     }
 }
 
-// One operand tile of ROWS rows x 64 k, fetched by the whole workgroup.
-template <int ROWS, bool KMAJOR>
+// One operand tile of ROWS rows x 64 k.  A k-contiguous tile is fetched by all NT threads
+// of the workgroup; a k-major tile by the ROWS threads [T0, T0+ROWS), one 8x8 block each.
+template <int ROWS, bool KMAJOR, int NT, int T0>
 struct TileLoader {
-  static constexpr int NCH = KMAJOR ? 8 : ROWS / 32;  // 16-byte registers per thread
+  static constexpr int NCH = KMAJOR ? 8 : ROWS * 8 / NT;  // 16-byte registers per thread
+  static_assert(KMAJOR || (ROWS * 8) % NT == 0, "tile rows must divide over the threads");
+  static_assert(!KMAJOR || T0 + ROWS <= NT, "not enough threads for the k-major tile");
   u32x4 r[NCH];
   uint32_t voff[NCH];  // byte offset of each load at k = 0 (kOob where the row is outside the operand)
   int kofs;            // this thread's k offset inside the 64-wide step (first of its loads)
   uint32_t kstride;    // bytes per unit of k
+
+  __device__ static inline bool mine(int t) { return !KMAJOR || (t >= T0 && t < T0 + ROWS); }
 
   __device__ inline void init(int row0, int rows, int ld, int t) {
     if constexpr (!KMAJOR) {
@@ -74,12 +79,13 @@ struct TileLoader {
       kstride = 2;
 #pragma unroll
       for (int i = 0; i < NCH; ++i) {
-        const int row = row0 + ((t + 256 * i) >> 3);
+        const int row = row0 + ((t + NT * i) >> 3);
         voff[i] = row < rows ? ((uint32_t)row * ld + kofs) * 2u : kOob;
       }
     } else {
-      const int mb = t % (ROWS / 8), kb = t / (ROWS / 8);
-      const bool on = (ROWS >= 256 || t < ROWS) && (row0 + mb * 8 < rows);
+      const int u = t - T0;
+      const int mb = u % (ROWS / 8), kb = u / (ROWS / 8);
+      const bool on = mine(t) && (row0 + mb * 8 < rows);
       kofs = kb * 8;
       kstride = (uint32_t)ld * 2u;
 #pragma unroll
@@ -88,7 +94,8 @@ struct TileLoader {
   }
 
   // k0: first k of this step in operand coordinates; kend: bound on k
-  __device__ inline void fetch(__amdgpu_buffer_rsrc_t rs, int k0, int kend) {
+  __device__ inline void fetch(__amdgpu_buffer_rsrc_t rs, int k0, int kend, int t) {
+    if (!mine(t)) return;
     const uint32_t adv = (uint32_t)k0 * kstride;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
@@ -101,12 +108,13 @@ struct TileLoader {
     if constexpr (!KMAJOR) {
 #pragma unroll
       for (int i = 0; i < NCH; ++i) {
-        const int c = t + 256 * i;
+        const int c = t + NT * i;
         *reinterpret_cast<u32x4 *>(lds + swz(c >> 3, c & 7)) = r[i];
       }
     } else {
-      if (ROWS >= 256 || t < ROWS) {
-        const int mb = t % (ROWS / 8), kb = t / (ROWS / 8);
+      if (mine(t)) {
+        const int u = t - T0;
+        const int mb = u % (ROWS / 8), kb = u / (ROWS / 8);
         u32x4 o[8];
         transpose8x8(r, o);
 #pragma unroll
@@ -130,17 +138,18 @@ __device__ inline u32x4 pack8(const float (&f)[8]) {
   return v;
 }
 
-template <int BM, int BN, bool AKM, bool BKM, int EPI>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
-  constexpr int WTM = BM / 2, WTN = BN / 2;   // wavefront tile
+template <int BM, int BN, int WGM, int WGN, bool AKM, bool BKM, int EPI>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g) {
+  constexpr int NT = 64 * WGM * WGN;          // threads
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;   // wavefront tile
   constexpr int MI = WTM / 32, NI = WTN / 32; // MFMA tiles per wavefront
   constexpr int STAGE = (BM + BN) * ROWB;
   constexpr int SP = WTN + 4;                 // epilogue staging row pitch, floats
-  static_assert(4 * 32 * SP * 4 <= 2 * STAGE, "epilogue staging must fit in the operand buffers");
+  static_assert(WGM * WGN * 32 * SP * 4 <= 2 * STAGE, "epilogue staging must fit in the operand buffers");
   __shared__ __attribute__((aligned(16))) char smem[2 * STAGE];
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WGN, wn = wave % WGN;
 
   // ---- tile id: XCD regrouping, then groups of 8 tile rows ----
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
@@ -155,8 +164,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   const int m0 = tm * BM, n0 = tn * BN;
 
   const __amdgpu_buffer_rsrc_t ra = make_rsrc(g.A, g.a_bytes), rb = make_rsrc(g.B, g.b_bytes);
-  TileLoader<BM, AKM> la;
-  TileLoader<BN, BKM> lb;
+  // when both tiles are k-major and there are threads to spare, different threads take A and B
+  constexpr int TB0 = (AKM && BKM && BM + BN <= NT) ? BM : 0;
+  TileLoader<BM, AKM, NT, 0> la;
+  TileLoader<BN, BKM, NT, TB0> lb;
   la.init(m0, g.M, g.lda, t);
   lb.init(n0, g.N, g.ldb, t);
   const int nk = (g.K + BK - 1) / BK;
@@ -169,8 +180,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
       ka = r; kenda = g.seg_len;
       kb = g.segs.row0[s] + r; kendb = g.segs.row0[s] + g.seg_len;
     }
-    la.fetch(ra, ka, kenda);
-    lb.fetch(rb, kb, kendb);
+    la.fetch(ra, ka, kenda, t);
+    lb.fetch(rb, kb, kendb, t);
   };
 
   floatx16 acc[MI][NI];
@@ -181,16 +192,25 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  // Pipeline: the tile for step kt+1 travels HBM -> registers during step kt-1..kt and is
+  // written to the idle LDS buffer at the top of step kt, while step kt's MFMAs read the other
+  // buffer; the tile for step kt+2 is requested right after.  One barrier per step.
   fetch(0);
   la.store(smem, t);
   lb.store(smem + BM * ROWB, t);
+  if (nk > 1) fetch(1);
   __syncthreads();
 
   const int frow = lane & 31, fchunk = lane >> 5;
   for (int kt = 0; kt < nk; ++kt) {
     const char *sa = smem + (kt & 1) * STAGE;
     const char *sb = sa + BM * ROWB;
-    if (kt + 1 < nk) fetch(kt + 1);
+    if (kt + 1 < nk) {
+      char *na = smem + ((kt + 1) & 1) * STAGE;
+      la.store(na, t);
+      lb.store(na + BM * ROWB, t);
+      if (kt + 2 < nk) fetch(kt + 2);
+    }
     // operand fragments are fetched from LDS one 16-wide k slice ahead of the MFMAs that use them
     bf16x8 af[2][MI], bfr[2][NI];
 #pragma unroll
@@ -215,11 +235,6 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
 #pragma unroll
         for (int j = 0; j < NI; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) {
-      char *na = smem + ((kt + 1) & 1) * STAGE;
-      la.store(na, t);
-      lb.store(na + BM * ROWB, t);
     }
     __syncthreads();
   }
@@ -301,19 +316,29 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   }
 }
 
-template <int BM, int BN, bool AKM, bool BKM, int EPI>
+template <int BM, int BN, int WGM, int WGN, bool AKM, bool BKM, int EPI>
 hipError_t launch(const GemmArgs &g, hipStream_t s) {
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
-  hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, AKM, BKM, EPI>), dim3(tiles), dim3(256), 0, s, g);
+  hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WGM, WGN, AKM, BKM, EPI>), dim3(tiles), dim3(64 * WGM * WGN), 0, s,
+                     g);
   return hipGetLastError();
 }
 
 template <bool AKM, bool BKM, int EPI>
 hipError_t pick_tile(const GemmArgs &g, hipStream_t s) {
   auto tiles = [&](int bm, int bn) { return (long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn); };
-  if (tiles(256, 256) >= 200) return launch<256, 256, AKM, BKM, EPI>(g, s);
-  if (tiles(256, 128) >= 200) return launch<256, 128, AKM, BKM, EPI>(g, s);
-  return launch<128, 128, AKM, BKM, EPI>(g, s);
+  if (g.tile == 1) return launch<256, 256, 2, 2, AKM, BKM, EPI>(g, s);
+  if (g.tile == 2) return launch<256, 256, 2, 4, AKM, BKM, EPI>(g, s);
+  if (g.tile == 3) return launch<128, 128, 2, 2, AKM, BKM, EPI>(g, s);
+  // Measured on MI355X: with enough 256x256 tiles to cover most of the 256 CUs the large tile
+  // wins (8 wavefronts when no operand needs the transposing fill, 4 otherwise); below that
+  // the 128x128 tile, two workgroups per CU, keeps more CUs busy.
+  if (AKM && BKM) {
+    if (tiles(256, 256) >= 200) return launch<256, 256, 2, 2, AKM, BKM, EPI>(g, s);
+  } else if (tiles(256, 256) >= 160) {
+    return launch<256, 256, 2, 4, AKM, BKM, EPI>(g, s);
+  }
+  return launch<128, 128, 2, 2, AKM, BKM, EPI>(g, s);
 }
 
 }  // namespace

@@ -619,6 +619,24 @@ int il_profile_read(il_ctx *c, int32_t cap, const char **names, int64_t *launche
   return cnt;
 }
 
+int il_test_gemm(int32_t dtype, const void *A, const void *B, int32_t M, int32_t N, int32_t K, int32_t lda,
+                 int32_t ldb, int32_t a_kmajor, int32_t b_kmajor, int32_t epi, void *C, void *C2, int32_t ldc,
+                 const void *bias, const float *res, const void *aux, int32_t aux_wrap, float scale,
+                 int32_t beta, int32_t tile, void *stream) {
+  if (!A || !B || !C || M < 1 || N < 1 || K < 1) return IL_E_ARG;
+  if (dtype != IL_F32 && dtype != IL_BF16) return IL_E_ARG;
+  if (epi < EPI_STORE || epi > EPI_WGRAD || tile < 0 || tile > 3) return IL_E_ARG;
+  if ((epi == EPI_BIAS || epi == EPI_BIAS_GELU || epi == EPI_BIAS_RES) && !bias) return IL_E_ARG;
+  if ((epi == EPI_BIAS_RES && !res) || (epi == EPI_BIAS_GELU && !C2)) return IL_E_ARG;
+  if (epi == EPI_GELU_BWD && (!aux || aux_wrap < 1)) return IL_E_ARG;
+  GemmArgs g = base_args();
+  g.A = A; g.B = B; g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb;
+  g.a_kmajor = a_kmajor != 0; g.b_kmajor = b_kmajor != 0; g.epi = epi; g.C = C; g.C2 = C2; g.ldc = ldc;
+  g.bias = bias; g.res = res; g.aux = aux; g.aux_wrap = aux_wrap; g.scale = scale; g.beta = beta; g.tile = tile;
+  const hipError_t e = dtype == IL_F32 ? gemm_f32(g, (hipStream_t)stream) : gemm_bf16(g, (hipStream_t)stream);
+  return e == hipSuccess ? IL_OK : (e == hipErrorInvalidValue ? IL_E_SHAPE : IL_E_HIP);
+}
+
 int il_free(il_ctx *c) {
   if (!c) return IL_E_ARG;
   for (auto &r : c->recs) { hipEventDestroy(r.e0); hipEventDestroy(r.e1); }
