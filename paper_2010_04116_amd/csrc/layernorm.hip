@@ -9,7 +9,7 @@ namespace {
 
 constexpr int kWaves = 4;         // rows in flight per 256-thread block
 constexpr int kMaxJ = 32;         // lane owns columns lane + 64*j, j < kMaxJ  (d <= 2048)
-constexpr int kLnBwdBlocks = 1024;
+constexpr int kLnBwdBlocks = 512;
 
 __device__ inline float wave_sum(float v) {
 #pragma unroll
@@ -57,76 +57,132 @@ __global__ __launch_bounds__(256) void ln_fwd_kernel(const float *__restrict__ x
   }
 }
 
-template <typename T>
+// Vector access helpers: V consecutive elements per lane (V = 4 when d % 256 == 0, else 1).
+template <typename T, int V> struct Vec;
+template <> struct Vec<float, 4> {
+  static __device__ inline void load(const float *p, float (&o)[4]) {
+    const float4 v = *reinterpret_cast<const float4 *>(p);
+    o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+  }
+  static __device__ inline void store(float *p, const float (&o)[4]) {
+    *reinterpret_cast<float4 *>(p) = make_float4(o[0], o[1], o[2], o[3]);
+  }
+};
+template <> struct Vec<bf16_t, 4> {
+  static __device__ inline void load(const bf16_t *p, float (&o)[4]) {
+    const uint2 v = *reinterpret_cast<const uint2 *>(p);
+    o[0] = bf16_to_f32((bf16_t)(v.x & 0xFFFF)); o[1] = bf16_to_f32((bf16_t)(v.x >> 16));
+    o[2] = bf16_to_f32((bf16_t)(v.y & 0xFFFF)); o[3] = bf16_to_f32((bf16_t)(v.y >> 16));
+  }
+  static __device__ inline void store(bf16_t *p, const float (&o)[4]) {
+    uint2 v;
+    v.x = (uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16);
+    v.y = (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16);
+    *reinterpret_cast<uint2 *>(p) = v;
+  }
+};
+template <typename T> struct Vec<T, 1> {
+  static __device__ inline void load(const T *p, float (&o)[1]) { o[0] = ld<T>(p); }
+  static __device__ inline void store(T *p, const float (&o)[1]) { st<T>(p, o[0]); }
+};
+
+// Lane owns columns (lane + 64 j) * V + (0..V-1), j < J.
+template <typename T, int V, int J>
 __global__ __launch_bounds__(256) void ln_bwd_kernel(const T *__restrict__ dy, const float *__restrict__ x,
                                                      const float *__restrict__ stats,
                                                      const T *__restrict__ gamma, int rows, int N, int d,
-                                                     float *G, T *Gb,
-                                                     StreamWeights sw, float *__restrict__ partials) {
-  __shared__ float red[kWaves][64];
+                                                     float *G, T *Gb, StreamWeights sw,
+                                                     float *__restrict__ partials) {
+  __shared__ float red[kWaves][64 * V];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  float dg[kMaxJ], db[kMaxJ], gm[kMaxJ];
+  float dg[J][V], db[J][V], gm[J][V];
 #pragma unroll
-  for (int j = 0; j < kMaxJ; ++j) {
-    int c = lane + 64 * j;
-    dg[j] = 0.f;
-    db[j] = 0.f;
-    gm[j] = (c < d) ? ld<T>(gamma + c) : 0.f;
+  for (int j = 0; j < J; ++j) {
+    const int c = (lane + 64 * j) * V;
+#pragma unroll
+    for (int e = 0; e < V; ++e) { dg[j][e] = 0.f; db[j][e] = 0.f; gm[j][e] = 0.f; }
+    if (c < d) Vec<T, V>::load(gamma + c, gm[j]);
   }
+  const float invd = 1.f / d;
   for (int row = blockIdx.x * kWaves + wave; row < rows; row += gridDim.x * kWaves) {
     const int tok = row % N;
     const float w = sw.w[row / N];
     const float mean = stats[2 * tok], rstd = stats[2 * tok + 1];
     const float *xr = x + (size_t)tok * d;
     const T *dyr = dy + (size_t)row * d;
-    float xh[kMaxJ], dxh[kMaxJ];
-    float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-    for (int j = 0; j < kMaxJ; ++j) {
-      int c = lane + 64 * j;
-      if (c < d) {
-        float dyv = ld<T>(dyr + c);
-        xh[j] = (xr[c] - mean) * rstd;
-        dxh[j] = dyv * gm[j];
-        s1 += dxh[j];
-        s2 += dxh[j] * xh[j];
-        dg[j] += w * dyv * xh[j];
-        db[j] += w * dyv;
-      } else {
-        xh[j] = 0.f;
-        dxh[j] = 0.f;
-      }
-    }
-    const float m1 = wave_sum(s1) / d, m2 = wave_sum(s2) / d;
     float *gr = G + (size_t)row * d;
     T *gbr = Gb + (size_t)row * d;
+    float xh[J][V], dxh[J][V], gv[J][V];
+    float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-    for (int j = 0; j < kMaxJ; ++j) {
-      int c = lane + 64 * j;
+    for (int j = 0; j < J; ++j) {
+      const int c = (lane + 64 * j) * V;
       if (c < d) {
-        float v = gr[c] + rstd * (dxh[j] - m1 - xh[j] * m2);
-        gr[c] = v;
-        st<T>(gbr + c, v);
+        float dyv[V];
+        Vec<T, V>::load(dyr + c, dyv);
+        Vec<float, V>::load(xr + c, xh[j]);
+        Vec<float, V>::load(gr + c, gv[j]);
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          xh[j][e] = (xh[j][e] - mean) * rstd;
+          dxh[j][e] = dyv[e] * gm[j][e];
+          s1 += dxh[j][e];
+          s2 += dxh[j][e] * xh[j][e];
+          dg[j][e] += w * dyv[e] * xh[j][e];
+          db[j][e] += w * dyv[e];
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < V; ++e) { xh[j][e] = 0.f; dxh[j][e] = 0.f; gv[j][e] = 0.f; }
+      }
+    }
+    const float m1 = wave_sum(s1) * invd, m2 = wave_sum(s2) * invd;
+#pragma unroll
+    for (int j = 0; j < J; ++j) {
+      const int c = (lane + 64 * j) * V;
+      if (c < d) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) gv[j][e] += rstd * (dxh[j][e] - m1 - xh[j][e] * m2);
+        Vec<float, V>::store(gr + c, gv[j]);
+        if ((const void *)Gb != (const void *)G) Vec<T, V>::store(gbr + c, gv[j]);
       }
     }
   }
-  // block-level column sums: waves 1..3 hand their registers to wave 0 through LDS
+  // block-level column sums: the four wavefronts combine through LDS, fixed order
   float *pg = partials + (size_t)blockIdx.x * 2 * d;
 #pragma unroll
-  for (int j = 0; j < kMaxJ; ++j) {
-    if (64 * j >= d) continue;  // uniform across the block
+  for (int j = 0; j < J; ++j) {
+    if (64 * j * V >= d) continue;  // uniform across the block
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
       __syncthreads();
-      red[wave][lane] = pass ? db[j] : dg[j];
+#pragma unroll
+      for (int e = 0; e < V; ++e) red[wave][lane * V + e] = pass ? db[j][e] : dg[j][e];
       __syncthreads();
       if (wave == 0) {
-        int c = lane + 64 * j;
-        float v = red[0][lane] + red[1][lane] + red[2][lane] + red[3][lane];
-        if (c < d) pg[pass * d + c] = v;
+        const int c = (lane + 64 * j) * V;
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          const int i = lane * V + e;
+          if (c + e < d) pg[pass * d + c + e] = (red[0][i] + red[1][i]) + (red[2][i] + red[3][i]);
+        }
       }
     }
   }
+}
+
+template <typename T>
+void launch_ln_bwd(int blocks, hipStream_t s, const void *dy, const float *x, const float *stats, const void *gamma,
+                   int rows, int N, int d, float *G, void *Gb, StreamWeights sw, float *partials) {
+#define IL_LN_BWD(V, J)                                                                                          \
+  hipLaunchKernelGGL((ln_bwd_kernel<T, V, J>), dim3(blocks), dim3(256), 0, s, (const T *)dy, x, stats,          \
+                     (const T *)gamma, rows, N, d, G, (T *)Gb, sw, partials)
+  if (d % 256 == 0 && d <= 512) IL_LN_BWD(4, 2);
+  else if (d % 256 == 0 && d <= 1024) IL_LN_BWD(4, 4);
+  else if (d % 256 == 0 && d <= 2048) IL_LN_BWD(4, 8);
+  else if (d <= 256) IL_LN_BWD(1, 4);
+  else IL_LN_BWD(1, 32);
+#undef IL_LN_BWD
 }
 
 }  // namespace
@@ -152,11 +208,9 @@ hipError_t ln_backward_residual(int dtype, const void *dy, const float *x, const
   if (blocks > kLnBwdBlocks) blocks = kLnBwdBlocks;
   *nblk = blocks;
   if (dtype == 0)
-    hipLaunchKernelGGL(ln_bwd_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float *)dy, x, stats,
-                       (const float *)gamma, rows, N, d, G, (float *)Gb, sw, partials);
+    launch_ln_bwd<float>(blocks, s, dy, x, stats, gamma, rows, N, d, G, Gb, sw, partials);
   else
-    hipLaunchKernelGGL(ln_bwd_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, (const bf16_t *)dy, x, stats,
-                       (const bf16_t *)gamma, rows, N, d, G, (bf16_t *)Gb, sw, partials);
+    launch_ln_bwd<bf16_t>(blocks, s, dy, x, stats, gamma, rows, N, d, G, Gb, sw, partials);
   return hipGetLastError();
 }
 

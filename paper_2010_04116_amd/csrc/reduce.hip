@@ -8,32 +8,67 @@ namespace {
 
 constexpr int kColBlocksY = 64;   // row splits of the first stage
 
-// grid (ceil(cols/64), nby); block 256 = 64 columns x 4 row lanes
-template <typename T>
+// First stage.  V = 8: grid (ceil(cols/256), nby), block = 32 column groups of 8 x 8 row
+// lanes, 16-byte loads (cols % 8 == 0).  V = 1: block = 64 columns x 4 row lanes.
+template <typename T, int V>
 __global__ __launch_bounds__(256) void colsum_partial_kernel(const T *__restrict__ Y, int rows, int N, int cols,
                                                              int ldy, StreamWeights sw,
                                                              float *__restrict__ partials) {
-  __shared__ float red[4][64];
-  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-  const int c = blockIdx.x * 64 + tx;
+  constexpr int CG = V == 8 ? 32 : 64, RL = 256 / CG;
+  __shared__ float red[RL][CG * V];
+  const int tx = threadIdx.x % CG, ty = threadIdx.x / CG;
+  const int c = (blockIdx.x * CG + tx) * V;
   const int per = (rows + gridDim.y - 1) / gridDim.y;
   const int r0 = blockIdx.y * per, r1 = min(rows, r0 + per);
-  float acc = 0.f;
+  float acc[V];
+#pragma unroll
+  for (int e = 0; e < V; ++e) acc[e] = 0.f;
   if (c < cols)
-    for (int r = r0 + ty; r < r1; r += 4) acc += sw.w[r / N] * ld<T>(Y + (size_t)r * ldy + c);
-  red[ty][tx] = acc;
+    for (int r = r0 + ty; r < r1; r += RL) {
+      const float w = sw.w[r / N];
+      if constexpr (V == 8) {
+        const uint4 v = *reinterpret_cast<const uint4 *>(Y + (size_t)r * ldy + c);
+        const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          acc[2 * e] += w * bf16_to_f32((bf16_t)(u[e] & 0xFFFF));
+          acc[2 * e + 1] += w * bf16_to_f32((bf16_t)(u[e] >> 16));
+        }
+      } else {
+        acc[0] += w * ld<T>(Y + (size_t)r * ldy + c);
+      }
+    }
+#pragma unroll
+  for (int e = 0; e < V; ++e) red[ty][tx * V + e] = acc[e];
   __syncthreads();
-  if (ty == 0 && c < cols)
-    partials[(size_t)blockIdx.y * cols + c] = red[0][tx] + red[1][tx] + red[2][tx] + red[3][tx];
+  for (int i = threadIdx.x; i < CG * V; i += 256) {
+    const int cc = blockIdx.x * CG * V + i;
+    if (cc < cols) {
+      float v = 0.f;
+#pragma unroll
+      for (int y = 0; y < RL; ++y) v += red[y][i];
+      partials[(size_t)blockIdx.y * cols + cc] = v;
+    }
+  }
 }
 
+// Second stage: block = 16 columns x 16 partial lanes; fixed summation order.
 __global__ __launch_bounds__(256) void colsum_final_kernel(const float *__restrict__ partials, int nblk, int cols,
                                                            float *__restrict__ out, int accumulate) {
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c >= cols) return;
-  float acc = accumulate ? out[c] : 0.f;
-  for (int p = 0; p < nblk; ++p) acc += partials[(size_t)p * cols + c];
-  out[c] = acc;
+  __shared__ float red[16][17];
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + tx;
+  float acc = 0.f;
+  if (c < cols)
+    for (int p = ty; p < nblk; p += 16) acc += partials[(size_t)p * cols + c];
+  red[ty][tx] = acc;
+  __syncthreads();
+  if (ty == 0 && c < cols) {
+    float v = accumulate ? out[c] : 0.f;
+#pragma unroll
+    for (int y = 0; y < 16; ++y) v += red[y][tx];
+    out[c] = v;
+  }
 }
 
 template <typename T>
@@ -97,18 +132,20 @@ hipError_t colsum_partial(int dtype, const void *Y, int rows, int N, int cols, i
   if (nby > kColBlocksY) nby = kColBlocksY;
   if (nby < 1) nby = 1;
   *nblk = nby;
-  dim3 grid((cols + 63) / 64, nby);
   if (dtype == 0)
-    hipLaunchKernelGGL(colsum_partial_kernel<float>, grid, dim3(256), 0, s, (const float *)Y, rows, N, cols,
-                       ldy, sw, partials);
+    hipLaunchKernelGGL((colsum_partial_kernel<float, 1>), dim3((cols + 63) / 64, nby), dim3(256), 0, s,
+                       (const float *)Y, rows, N, cols, ldy, sw, partials);
+  else if ((cols & 7) == 0 && (ldy & 7) == 0)
+    hipLaunchKernelGGL((colsum_partial_kernel<bf16_t, 8>), dim3((cols + 255) / 256, nby), dim3(256), 0, s,
+                       (const bf16_t *)Y, rows, N, cols, ldy, sw, partials);
   else
-    hipLaunchKernelGGL(colsum_partial_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)Y, rows, N, cols,
-                       ldy, sw, partials);
+    hipLaunchKernelGGL((colsum_partial_kernel<bf16_t, 1>), dim3((cols + 63) / 64, nby), dim3(256), 0, s,
+                       (const bf16_t *)Y, rows, N, cols, ldy, sw, partials);
   return hipGetLastError();
 }
 
 hipError_t colsum_final(const float *partials, int nblk, int cols, float *out, int accumulate, hipStream_t s) {
-  hipLaunchKernelGGL(colsum_final_kernel, dim3((cols + 255) / 256), dim3(256), 0, s, partials, nblk, cols, out,
+  hipLaunchKernelGGL(colsum_final_kernel, dim3((cols + 15) / 16), dim3(256), 0, s, partials, nblk, cols, out,
                      accumulate);
   return hipGetLastError();
 }
