@@ -66,7 +66,7 @@ struct TileLoader {
   static constexpr int NCH = KMAJOR ? 8 : ROWS * 8 / NT;  // 16-byte registers per thread
   static_assert(KMAJOR || (ROWS * 8) % NT == 0, "tile rows must divide over the threads");
   static_assert(!KMAJOR || T0 + ROWS <= NT, "not enough threads for the k-major tile");
-  u32x4 r[NCH];
+  struct Regs { u32x4 r[NCH]; };
   uint32_t voff[NCH];  // byte offset of each load at k = 0 (kOob where the row is outside the operand)
   int kofs;            // this thread's k offset inside the 64-wide step (first of its loads)
   uint32_t kstride;    // bytes per unit of k
@@ -94,29 +94,29 @@ struct TileLoader {
   }
 
   // k0: first k of this step in operand coordinates; kend: bound on k
-  __device__ inline void fetch(__amdgpu_buffer_rsrc_t rs, int k0, int kend, int t) {
+  __device__ inline void fetch(Regs &x, __amdgpu_buffer_rsrc_t rs, int k0, int kend, int t) const {
     if (!mine(t)) return;
     const uint32_t adv = (uint32_t)k0 * kstride;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const bool ok = k0 + kofs + (KMAJOR ? i : 0) < kend;
-      r[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, ok ? voff[i] + adv : kOob, 0, 0);
+      x.r[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, ok ? voff[i] + adv : kOob, 0, 0);
     }
   }
 
-  __device__ inline void store(char *lds, int t) const {
+  __device__ inline void store(const Regs &x, char *lds, int t) const {
     if constexpr (!KMAJOR) {
 #pragma unroll
       for (int i = 0; i < NCH; ++i) {
         const int c = t + NT * i;
-        *reinterpret_cast<u32x4 *>(lds + swz(c >> 3, c & 7)) = r[i];
+        *reinterpret_cast<u32x4 *>(lds + swz(c >> 3, c & 7)) = x.r[i];
       }
     } else {
       if (mine(t)) {
         const int u = t - T0;
         const int mb = u % (ROWS / 8), kb = u / (ROWS / 8);
         u32x4 o[8];
-        transpose8x8(r, o);
+        transpose8x8(x.r, o);
 #pragma unroll
         for (int c = 0; c < 8; ++c) *reinterpret_cast<u32x4 *>(lds + swz(mb * 8 + c, kb)) = o[c];
       }
@@ -138,107 +138,13 @@ __device__ inline u32x4 pack8(const float (&f)[8]) {
   return v;
 }
 
-template <int BM, int BN, int WGM, int WGN, bool AKM, bool BKM, int EPI>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g) {
-  constexpr int NT = 64 * WGM * WGN;          // threads
-  constexpr int WTM = BM / WGM, WTN = BN / WGN;   // wavefront tile
-  constexpr int MI = WTM / 32, NI = WTN / 32; // MFMA tiles per wavefront
-  constexpr int STAGE = (BM + BN) * ROWB;
-  constexpr int SP = WTN + 4;                 // epilogue staging row pitch, floats
-  static_assert(WGM * WGN * 32 * SP * 4 <= 2 * STAGE, "epilogue staging must fit in the operand buffers");
-  __shared__ __attribute__((aligned(16))) char smem[2 * STAGE];
-
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+// ---- epilogue shared by both kernels ------------------------------------------------------
+template <int BM, int BN, int WGM, int WGN, int EPI, int MI, int NI>
+__device__ inline void epilogue(const GemmArgs &g, floatx16 (&acc)[MI][NI], char *smem, int m0, int n0, int wave,
+                                int lane) {
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int SP = WTN + 4;
   const int wm = wave / WGN, wn = wave % WGN;
-
-  // ---- tile id: XCD regrouping, then groups of 8 tile rows ----
-  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-  const int total = tiles_m * tiles_n;
-  int pid = blockIdx.x;
-  if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);
-  constexpr int GM = 8;
-  const int per_group = GM * tiles_n;
-  const int group = pid / per_group, first_m = group * GM;
-  const int gsize = min(tiles_m - first_m, GM);
-  const int tm = first_m + (pid % per_group) % gsize, tn = (pid % per_group) / gsize;
-  const int m0 = tm * BM, n0 = tn * BN;
-
-  const __amdgpu_buffer_rsrc_t ra = make_rsrc(g.A, g.a_bytes), rb = make_rsrc(g.B, g.b_bytes);
-  // when both tiles are k-major and there are threads to spare, different threads take A and B
-  constexpr int TB0 = (AKM && BKM && BM + BN <= NT) ? BM : 0;
-  TileLoader<BM, AKM, NT, 0> la;
-  TileLoader<BN, BKM, NT, TB0> lb;
-  la.init(m0, g.M, g.lda, t);
-  lb.init(n0, g.N, g.ldb, t);
-  const int nk = (g.K + BK - 1) / BK;
-  const bool seg = AKM && BKM && g.segs.nseg > 0;
-
-  auto fetch = [&](int kt) {
-    int ka = kt * BK, kb = ka, kenda = g.K, kendb = g.K;
-    if (seg) {  // segmented reduction: a K step never straddles two segments
-      const int s = ka / g.seg_len, r = ka % g.seg_len;
-      ka = r; kenda = g.seg_len;
-      kb = g.segs.row0[s] + r; kendb = g.segs.row0[s] + g.seg_len;
-    }
-    la.fetch(ra, ka, kenda, t);
-    lb.fetch(rb, kb, kendb, t);
-  };
-
-  floatx16 acc[MI][NI];
-#pragma unroll
-  for (int i = 0; i < MI; ++i)
-#pragma unroll
-    for (int j = 0; j < NI; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  // Pipeline: the tile for step kt+1 travels HBM -> registers during step kt-1..kt and is
-  // written to the idle LDS buffer at the top of step kt, while step kt's MFMAs read the other
-  // buffer; the tile for step kt+2 is requested right after.  One barrier per step.
-  fetch(0);
-  la.store(smem, t);
-  lb.store(smem + BM * ROWB, t);
-  if (nk > 1) fetch(1);
-  __syncthreads();
-
-  const int frow = lane & 31, fchunk = lane >> 5;
-  for (int kt = 0; kt < nk; ++kt) {
-    const char *sa = smem + (kt & 1) * STAGE;
-    const char *sb = sa + BM * ROWB;
-    if (kt + 1 < nk) {
-      char *na = smem + ((kt + 1) & 1) * STAGE;
-      la.store(na, t);
-      lb.store(na + BM * ROWB, t);
-      if (kt + 2 < nk) fetch(kt + 2);
-    }
-    // operand fragments are fetched from LDS one 16-wide k slice ahead of the MFMAs that use them
-    bf16x8 af[2][MI], bfr[2][NI];
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-      af[0][i] = *reinterpret_cast<const bf16x8 *>(sa + swz(wm * WTM + i * 32 + frow, fchunk));
-#pragma unroll
-    for (int j = 0; j < NI; ++j)
-      bfr[0][j] = *reinterpret_cast<const bf16x8 *>(sb + swz(wn * WTN + j * 32 + frow, fchunk));
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      const int cur = ks & 1, nxt = cur ^ 1;
-      if (ks + 1 < BK / 16) {
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-          af[nxt][i] = *reinterpret_cast<const bf16x8 *>(sa + swz(wm * WTM + i * 32 + frow, 2 * (ks + 1) + fchunk));
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-          bfr[nxt][j] = *reinterpret_cast<const bf16x8 *>(sb + swz(wn * WTN + j * 32 + frow, 2 * (ks + 1) + fchunk));
-      }
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
-    }
-    __syncthreads();
-  }
-
   // ---- epilogue.  A lane holds column (lane & 31) and rows 8*(r/4) + 4*(lane>>5) + (r&3) of
   // each 32x32 tile; each wavefront passes one 32-row strip at a time through its own LDS
   // region so that every lane ends up with 8 consecutive columns of one row: 16-byte bf16 /
@@ -316,10 +222,306 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g) {
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, bool AKM, bool BKM, int EPI>
+template <int BM, int BN, int WGM, int WGN, int PF, bool AKM, bool BKM, int EPI>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g) {
+  constexpr int NT = 64 * WGM * WGN;          // threads
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;   // wavefront tile
+  constexpr int MI = WTM / 32, NI = WTN / 32; // MFMA tiles per wavefront
+  constexpr int STAGE = (BM + BN) * ROWB;
+  constexpr int SP = WTN + 4;                 // epilogue staging row pitch, floats
+  static_assert(WGM * WGN * 32 * SP * 4 <= 2 * STAGE, "epilogue staging must fit in the operand buffers");
+  __shared__ __attribute__((aligned(16))) char smem[2 * STAGE];
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+
+  // ---- tile id: XCD regrouping, then groups of 8 tile rows ----
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+  const int total = tiles_m * tiles_n;
+  int pid = blockIdx.x;
+  if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);
+  constexpr int GM = 8;
+  const int per_group = GM * tiles_n;
+  const int group = pid / per_group, first_m = group * GM;
+  const int gsize = min(tiles_m - first_m, GM);
+  const int tm = first_m + (pid % per_group) % gsize, tn = (pid % per_group) / gsize;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  const __amdgpu_buffer_rsrc_t ra = make_rsrc(g.A, g.a_bytes), rb = make_rsrc(g.B, g.b_bytes);
+  // when both tiles are k-major and there are threads to spare, different threads take A and B
+  constexpr int TB0 = (AKM && BKM && BM + BN <= NT) ? BM : 0;
+  TileLoader<BM, AKM, NT, 0> la;
+  TileLoader<BN, BKM, NT, TB0> lb;
+  la.init(m0, g.M, g.lda, t);
+  lb.init(n0, g.N, g.ldb, t);
+  const int nk = (g.K + BK - 1) / BK;
+  const bool seg = AKM && BKM && g.segs.nseg > 0;
+
+  typename TileLoader<BM, AKM, NT, 0>::Regs xa[PF];
+  typename TileLoader<BN, BKM, NT, TB0>::Regs xb[PF];
+  auto fetch = [&](int kt, int slot) {
+    int ka = kt * BK, kb = ka, kenda = g.K, kendb = g.K;
+    if (seg) {  // segmented reduction: a K step never straddles two segments
+      const int s = ka / g.seg_len, r = ka % g.seg_len;
+      ka = r; kenda = g.seg_len;
+      kb = g.segs.row0[s] + r; kendb = g.segs.row0[s] + g.seg_len;
+    }
+    la.fetch(xa[slot], ra, ka, kenda, t);
+    lb.fetch(xb[slot], rb, kb, kendb, t);
+  };
+
+  floatx16 acc[MI][NI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // Pipeline: PF K steps are in flight HBM -> registers at any time (enough bytes outstanding
+  // to cover the memory latency, which a single step of a small tile does not).  The tile for
+  // step kt+1 is written to the idle LDS buffer at the top of step kt, while step kt's MFMAs
+  // read the other buffer, and its registers are refilled with step kt+1+PF.  One barrier per
+  // step.  Step j+1 travels in register slot j % PF.
+  fetch(0, 0);
+  la.store(xa[0], smem, t);
+  lb.store(xb[0], smem + BM * ROWB, t);
+#pragma unroll
+  for (int sl = 0; sl < PF; ++sl)
+    if (1 + sl < nk) fetch(1 + sl, sl);
+  __syncthreads();
+
+  const int frow = lane & 31, fchunk = lane >> 5;
+  for (int kt0 = 0; kt0 < nk; kt0 += PF) {
+#pragma unroll
+   for (int sl = 0; sl < PF; ++sl) {
+    const int kt = kt0 + sl;
+    if (kt >= nk) break;
+    const char *sa = smem + (kt & 1) * STAGE;
+    const char *sb = sa + BM * ROWB;
+    if (kt + 1 < nk && !(g.tile & 16)) {
+      char *na = smem + ((kt + 1) & 1) * STAGE;
+      la.store(xa[sl], na, t);
+      lb.store(xb[sl], na + BM * ROWB, t);
+      if (kt + 1 + PF < nk) fetch(kt + 1 + PF, sl);
+    }
+    // operand fragments are fetched from LDS one 16-wide k slice ahead of the MFMAs that use them
+    bf16x8 af[2][MI], bfr[2][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+      af[0][i] = *reinterpret_cast<const bf16x8 *>(sa + swz(wm * WTM + i * 32 + frow, fchunk));
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+      bfr[0][j] = *reinterpret_cast<const bf16x8 *>(sb + swz(wn * WTN + j * 32 + frow, fchunk));
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      const int cur = ks & 1, nxt = cur ^ 1;
+      if (ks + 1 < BK / 16) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+          af[nxt][i] = *reinterpret_cast<const bf16x8 *>(sa + swz(wm * WTM + i * 32 + frow, 2 * (ks + 1) + fchunk));
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+          bfr[nxt][j] = *reinterpret_cast<const bf16x8 *>(sb + swz(wn * WTN + j * 32 + frow, 2 * (ks + 1) + fchunk));
+      }
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
+    }
+    __syncthreads();
+   }
+  }
+
+  epilogue<BM, BN, WGM, WGN, EPI>(g, acc, smem, m0, n0, wave, lane);
+}
+
+// ------------------------------------------------------------------------------------------
+// Variant with direct HBM -> LDS operand staging (buffer loads with LDS destination) and,
+// for k-major operands, the LDS transposing read.  No staging registers, so NSTAGE LDS
+// buffers of BKT-wide K steps can be in flight.
+//
+// Direct loads write 16 bytes per lane at consecutive LDS addresses in lane order, so the
+// LDS image of a tile is fixed and the swizzle is applied on the global side: the thread that
+// fills LDS chunk position p fetches the logical chunk that belongs there.
+//   k-contiguous tile: [row][BKT] (BKT*2 bytes per row), chunk c of row r at c ^ g(r)
+//   k-major tile:      [k][ROWS]  (ROWS*2 bytes per k),  chunk c of k-row k at c ^ 2(k & 3)
+// A k-major fragment is two ds_read_b64_tr_b16: within 16 lanes, lane i points at 4
+// consecutive rows-elements of k-row kb + i/4, column group 4(i%4); the instruction hands
+// lane j the four k values kb..kb+3 of row j - exactly the MFMA operand order.
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4v;
+typedef __attribute__((address_space(3))) void lds_void;
+
+template <int ROWS, int BKT, bool KMAJOR, int NT>
+struct DmaTile {
+  static constexpr int BYTES = ROWS * BKT * 2;
+  static constexpr int NLD = BYTES / (NT * 16);  // loads per thread per K step
+  static_assert(BYTES % (NT * 16) == 0 && NLD >= 1, "tile must divide over the threads");
+  static constexpr int RB = KMAJOR ? ROWS * 2 : BKT * 2;  // LDS bytes per row
+  uint32_t voff[NLD];
+  int kadd[NLD];
+  uint32_t kstride;
+
+  __device__ static inline int g(int row) { return BKT == 64 ? ((row ^ (row >> 3)) & 7) : ((row >> 1) & 3); }
+
+  __device__ inline void init(int row0, int rows, int ld, int t) {
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int p = i * NT + t;
+      if constexpr (!KMAJOR) {
+        constexpr int CPR = BKT / 8;
+        const int row = p / CPR, chunk = (p % CPR) ^ g(row);
+        kadd[i] = chunk * 8;
+        voff[i] = row0 + row < rows ? ((uint32_t)(row0 + row) * ld + chunk * 8) * 2u : kOob;
+        kstride = 2;
+      } else {
+        constexpr int CPR = ROWS / 8;
+        const int krow = p / CPR, chunk = (p % CPR) ^ (2 * (krow & 3));
+        kadd[i] = krow;
+        voff[i] = row0 + chunk * 8 < rows ? ((uint32_t)krow * ld + row0 + chunk * 8) * 2u : kOob;
+        kstride = (uint32_t)ld * 2u;
+      }
+    }
+  }
+  // lds: stage base of this operand (wave-uniform); wave: wave id (uniform)
+  __device__ inline void issue(__amdgpu_buffer_rsrc_t rs, char *lds, int wave, int k0, int kend) const {
+    const uint32_t adv = (uint32_t)k0 * kstride;
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const bool ok = k0 + kadd[i] < kend;
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass cannot type-check this builtin (it only needs the kernel's stub)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(lds + (i * NT + wave * 64) * 16), 16,
+                                               ok ? voff[i] + adv : kOob, 0, 0, 0);
+#else
+      (void)rs; (void)lds; (void)wave; (void)ok; (void)adv;
+#endif
+    }
+  }
+  // 32 x 16 MFMA fragment of rows [rbase, rbase+32), k slice ks of the staged K step
+  __device__ static inline bf16x8 frag(const char *lds, int rbase, int ks, int lane) {
+    if constexpr (!KMAJOR) {
+      const int row = rbase + (lane & 31), chunk = 2 * ks + (lane >> 5);
+      return *reinterpret_cast<const bf16x8 *>(lds + row * RB + ((chunk ^ g(row)) << 4));
+    } else {
+      const int g16 = lane >> 4, i = lane & 15;
+      const int m = rbase + 16 * (g16 & 1) + 4 * (i & 3);
+      const int k = 16 * ks + 8 * (g16 >> 1) + (i >> 2);
+      const int col = (((m >> 3) ^ (2 * (i >> 2))) << 4) + ((m >> 2) & 1) * 8;
+      union { short4v h[2]; bf16x8 v; } f;
+      f.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) short4v *)(lds + k * RB + col));
+      f.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+          (__attribute__((address_space(3))) short4v *)(lds + (k + 4) * RB + col));
+      return f.v;
+    }
+  }
+};
+
+constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
+
+template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGE, bool AKM, bool BKM, int EPI>
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmArgs g) {
+  constexpr int NT = 64 * WGM * WGN;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int MI = WTM / 32, NI = WTN / 32;
+  constexpr int ABYTES = BM * BKT * 2, STAGE = (BM + BN) * BKT * 2;
+  constexpr int SP = WTN + 4;
+  static_assert(WGM * WGN * 32 * SP * 4 <= NSTAGE * STAGE, "epilogue staging must fit in the operand buffers");
+  __shared__ __attribute__((aligned(16))) char smem[NSTAGE * STAGE];
+
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wave / WGN, wn = wave % WGN;
+
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+  const int total = tiles_m * tiles_n;
+  int pid = blockIdx.x;
+  if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);
+  constexpr int GM = 8;
+  const int per_group = GM * tiles_n;
+  const int group = pid / per_group, first_m = group * GM;
+  const int gsize = min(tiles_m - first_m, GM);
+  const int tm = first_m + (pid % per_group) % gsize, tn = (pid % per_group) / gsize;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  const __amdgpu_buffer_rsrc_t ra = make_rsrc(g.A, g.a_bytes), rb = make_rsrc(g.B, g.b_bytes);
+  typedef DmaTile<BM, BKT, AKM, NT> TA;
+  typedef DmaTile<BN, BKT, BKM, NT> TB;
+  TA la;
+  TB lb;
+  la.init(m0, g.M, g.lda, t);
+  lb.init(n0, g.N, g.ldb, t);
+  constexpr int LPS = TA::NLD + TB::NLD;  // loads per thread per K step
+  const int nk = (g.K + BKT - 1) / BKT;
+  const bool seg = AKM && BKM && g.segs.nseg > 0;
+
+  auto issue = [&](int kt) {
+    char *st = smem + (kt % NSTAGE) * STAGE;
+    int ka = kt * BKT, kb = ka, kenda = g.K, kendb = g.K;
+    if (seg) {
+      const int s = ka / g.seg_len, r = ka % g.seg_len;
+      ka = r; kenda = g.seg_len;
+      kb = g.segs.row0[s] + r; kendb = g.segs.row0[s] + g.seg_len;
+    }
+    la.issue(ra, st, wave, ka, kenda);
+    lb.issue(rb, st + ABYTES, wave, kb, kendb);
+  };
+
+  floatx16 acc[MI][NI];
+#pragma unroll
+  for (int i = 0; i < MI; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // K steps kt .. kt+NSTAGE-2 are in flight while step kt is multiplied; one barrier per step:
+  // it publishes step kt (every thread waited for its own loads of it) and retires the buffer
+  // of step kt-1, which the loads issued right after it overwrite.
+#pragma unroll
+  for (int s = 0; s < NSTAGE - 1; ++s)
+    if (s < nk) issue(s);
+
+  for (int kt = 0; kt < nk; ++kt) {
+    if (nk - 1 - kt >= NSTAGE - 2)
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm((NSTAGE - 2) * LPS));
+    else
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    __syncthreads();
+    if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
+    const char *sa = smem + (kt % NSTAGE) * STAGE;
+    const char *sb = sa + ABYTES;
+#pragma unroll
+    for (int ks = 0; ks < BKT / 16; ++ks) {
+      bf16x8 af[MI], bfr[NI];
+#pragma unroll
+      for (int i = 0; i < MI; ++i) af[i] = TA::frag(sa, wm * WTM + i * 32, ks, lane);
+#pragma unroll
+      for (int j = 0; j < NI; ++j) bfr[j] = TB::frag(sb, wn * WTN + j * 32, ks, lane);
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+  }
+  __syncthreads();
+  epilogue<BM, BN, WGM, WGN, EPI>(g, acc, smem, m0, n0, wave, lane);
+}
+
+template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGE, bool AKM, bool BKM, int EPI>
+hipError_t launch_dma(const GemmArgs &g, hipStream_t s) {
+  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, BKT, NSTAGE, AKM, BKM, EPI>), dim3(tiles),
+                     dim3(64 * WGM * WGN), 0, s, g);
+  return hipGetLastError();
+}
+
+template <int BM, int BN, int WGM, int WGN, int PF, bool AKM, bool BKM, int EPI>
 hipError_t launch(const GemmArgs &g, hipStream_t s) {
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
-  hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WGM, WGN, AKM, BKM, EPI>), dim3(tiles), dim3(64 * WGM * WGN), 0, s,
+  hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WGM, WGN, PF, AKM, BKM, EPI>), dim3(tiles), dim3(64 * WGM * WGN), 0, s,
                      g);
   return hipGetLastError();
 }
@@ -327,18 +529,27 @@ hipError_t launch(const GemmArgs &g, hipStream_t s) {
 template <bool AKM, bool BKM, int EPI>
 hipError_t pick_tile(const GemmArgs &g, hipStream_t s) {
   auto tiles = [&](int bm, int bn) { return (long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn); };
-  if (g.tile == 1) return launch<256, 256, 2, 2, AKM, BKM, EPI>(g, s);
-  if (g.tile == 2) return launch<256, 256, 2, 4, AKM, BKM, EPI>(g, s);
-  if (g.tile == 3) return launch<128, 128, 2, 2, AKM, BKM, EPI>(g, s);
+  switch (g.tile & 15) {
+    case 4: return launch_dma<256, 256, 2, 2, 64, 2, AKM, BKM, EPI>(g, s);
+    case 5: return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI>(g, s);
+    case 6: return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI>(g, s);
+    case 7: return launch_dma<256, 256, 2, 2, 32, 4, AKM, BKM, EPI>(g, s);
+    case 8: return launch_dma<256, 256, 2, 4, 32, 4, AKM, BKM, EPI>(g, s);
+    case 9: return launch_dma<128, 128, 2, 2, 32, 4, AKM, BKM, EPI>(g, s);
+    default: break;
+  }
+  if ((g.tile & 15) == 1) return launch<256, 256, 2, 2, 1, AKM, BKM, EPI>(g, s);
+  if ((g.tile & 15) == 2) return launch<256, 256, 2, 4, 1, AKM, BKM, EPI>(g, s);
+  if ((g.tile & 15) == 3) return launch<128, 128, 2, 2, 1, AKM, BKM, EPI>(g, s);
   // Measured on MI355X: with enough 256x256 tiles to cover most of the 256 CUs the large tile
   // wins (8 wavefronts when no operand needs the transposing fill, 4 otherwise); below that
   // the 128x128 tile, two workgroups per CU, keeps more CUs busy.
   if (AKM && BKM) {
-    if (tiles(256, 256) >= 200) return launch<256, 256, 2, 2, AKM, BKM, EPI>(g, s);
+    if (tiles(256, 256) >= 200) return launch<256, 256, 2, 2, 1, AKM, BKM, EPI>(g, s);
   } else if (tiles(256, 256) >= 160) {
-    return launch<256, 256, 2, 4, AKM, BKM, EPI>(g, s);
+    return launch<256, 256, 2, 4, 1, AKM, BKM, EPI>(g, s);
   }
-  return launch<128, 128, 2, 2, AKM, BKM, EPI>(g, s);
+  return launch<128, 128, 2, 2, 1, AKM, BKM, EPI>(g, s);
 }
 
 }  // namespace

@@ -1,0 +1,115 @@
+"""Kernel-level parity of the bf16 MFMA GEMM (every tile configuration, operand layout and
+epilogue the step uses, ragged edges, segmented weight-gradient reduction) against a float64
+matrix product of the same bf16-rounded operands.  Through the C ABI's il_test_gemm hook."""
+import numpy as np
+import pytest
+
+from paper_2010_04116_amd import binding as b, synth
+
+pytestmark = pytest.mark.gpu
+TILES = [1, 2, 3, 4, 5, 6, 7, 8, 9]
+
+
+def _bf16(a):
+    return synth.round_to_bf16(a.astype(np.float32))
+
+
+def _gelu(u):
+    return 0.5 * u * (1 + np.tanh(np.sqrt(2 / np.pi) * (u + 0.044715 * u ** 3)))
+
+
+def _gelu_grad(u):
+    t = np.tanh(np.sqrt(2 / np.pi) * (u + 0.044715 * u ** 3))
+    return 0.5 * (1 + t) + 0.5 * u * (1 - t * t) * np.sqrt(2 / np.pi) * (1 + 3 * 0.044715 * u * u)
+
+
+def run_case(M, N, K, akm, bkm, epi, tile, seed=0, beta=0, scale=1.0):
+    import torch
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(seed)
+    A = _bf16(rng.standard_normal((M, K)) * 0.5)
+    B = _bf16(rng.standard_normal((K, N)) * 0.5)
+    bias = _bf16(rng.standard_normal(N) * 0.5)
+    res = rng.standard_normal((M, N)).astype(np.float32)
+    aux_rows = max(1, M // 2)
+    aux = _bf16(rng.standard_normal((aux_rows, N)))
+    c0 = rng.standard_normal((M, N)).astype(np.float32)
+    acc = A.astype(np.float64) @ B.astype(np.float64)
+    tb = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(torch.bfloat16).to(dev)
+    tf = lambda x: torch.from_numpy(np.ascontiguousarray(x)).to(dev)
+    dA = tb(A.T if akm else A)
+    dB = tb(B if bkm else B.T)
+    f32out = epi in (3, 5, 6)
+    C = tf(c0) if f32out else torch.zeros((M, N), dtype=torch.bfloat16, device=dev)
+    C2 = torch.zeros((M, N), dtype=torch.bfloat16, device=dev)
+    b.il_test_gemm(b.IL_BF16, dA, dB, M, N, K, M if akm else K, N if bkm else K, akm, bkm, epi, C, C2=C2,
+                   ldc=N, bias=tb(bias), res=tf(res), aux=tb(aux), aux_wrap=aux_rows, scale=scale, beta=beta,
+                   tile=tile, stream=torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    got = C.float().cpu().numpy().astype(np.float64)
+    if epi == 0:
+        want = acc
+    elif epi == 1:
+        want = acc + bias
+    elif epi == 2:
+        want = acc + bias
+        got2 = C2.float().cpu().numpy().astype(np.float64)
+        want2 = _gelu(_bf16(want).astype(np.float64))
+        assert np.linalg.norm(got2 - want2) <= 6e-3 * np.linalg.norm(want2)
+    elif epi == 3:
+        want = acc + bias + res
+    elif epi == 4:
+        want = acc * _gelu_grad(aux.astype(np.float64))[np.arange(M) % aux_rows]
+    elif epi == 5:
+        want = acc
+    else:
+        want = scale * acc + (c0 if beta else 0)
+    tol = 1e-5 if f32out else 6e-3       # fp32 outputs: accumulation order only; bf16: one rounding
+    err = np.linalg.norm(got - want) / np.linalg.norm(want)
+    assert err <= tol, f"M={M} N={N} K={K} akm={akm} bkm={bkm} epi={epi} tile={tile}: rel err {err:.3e}"
+    if not f32out:
+        assert np.max(np.abs(got - want)) <= 2 ** -7 * np.max(np.abs(want)) + 1e-6
+
+
+@pytest.mark.parametrize("tile", TILES)
+def test_forward_layout_all_epilogues(tile):
+    for epi in (0, 1, 2, 3):
+        run_case(384, 264, 192, 0, 1, epi, tile, seed=epi)
+
+
+@pytest.mark.parametrize("tile", TILES)
+def test_dgrad_layout_all_epilogues(tile):
+    for epi in (0, 4, 5):
+        run_case(520, 136, 320, 0, 0, epi, tile, seed=10 + epi)
+
+
+@pytest.mark.parametrize("tile", TILES)
+def test_wgrad_layout(tile):
+    run_case(200, 392, 256, 1, 1, 6, tile, seed=20, beta=0, scale=0.5)
+    run_case(200, 392, 256, 1, 1, 6, tile, seed=21, beta=1, scale=1.0)
+
+
+@pytest.mark.parametrize("tile", TILES)
+def test_k_tail_and_tiny_sizes(tile):
+    run_case(8, 8, 8, 0, 0, 0, tile, seed=30)
+    run_case(72, 40, 104, 0, 1, 1, tile, seed=31)      # K not a multiple of 32 or 64
+    run_case(72, 40, 104, 0, 0, 5, tile, seed=32)
+    run_case(40, 72, 72, 1, 1, 6, tile, seed=33)
+
+
+@pytest.mark.parametrize("tile", [0, 2, 5, 8])
+def test_multi_tile_shapes(tile):
+    run_case(1024, 768, 512, 0, 1, 1, tile, seed=40)
+    run_case(1024, 768, 512, 0, 0, 0, tile, seed=41)
+    run_case(512, 1024, 2048, 1, 1, 6, tile, seed=42)
+
+
+def test_unsupported_combinations_are_rejected():
+    import torch
+    dev = torch.device("cuda:0")
+    x = torch.zeros((64, 64), dtype=torch.bfloat16, device=dev)
+    with pytest.raises(b.InterlockError) as e:       # k-major A with k-contiguous B is not a layout the step uses
+        b.il_test_gemm(b.IL_BF16, x, x, 64, 64, 64, 64, 64, 1, 0, 0, x)
+    assert e.value.status == b.IL_E_SHAPE
+    with pytest.raises(b.InterlockError):            # N not a multiple of 8
+        b.il_test_gemm(b.IL_BF16, x, x, 64, 60, 64, 64, 64, 0, 0, 0, x, ldc=64)
