@@ -3,23 +3,18 @@
 //
 // Tiling.  A workgroup of WGM x WGN wavefronts owns a BM x BN tile of C and walks K in steps
 // of 64.  Each wavefront owns (BM/WGM) x (BN/WGN) = MI x NI MFMA tiles of 32x32, all held in
-// accumulator registers.  Instantiated: 256x256 with 4 or 8 wavefronts, 128x128 with 4.  Both operand tiles are staged in LDS
-// as [row][64 k] bf16 with k contiguous (128 B per row), double buffered; the next K step
-// is fetched from HBM into registers while the current one is multiplied.
+// accumulator registers.  Instantiated: 256x256 with 4 or 8 wavefronts, 128x128 with 4.
 //
 // Operand layouts.  An operand is either "k-contiguous" ([rows, K] row-major: activations
 // in forward / dgrad, weights in dgrad) or "k-major" ([K, rows] row-major: weights in
-// forward, both operands of a weight gradient).  K-major tiles are transposed on the way
-// into LDS: a thread loads an 8(k) x 8(row) block as eight 16-byte rows, transposes it in
-// registers and writes eight 16-byte k-vectors, so the MFMA operand fetch from LDS is one
-// ds_read_b128 per 32x16 fragment in every case.
+// forward, both operands of a weight gradient).
 //
-// Loads.  Operands are read through raw buffer descriptors sized to the operand, so rows or
-// k beyond the edge read as zero without a branch.
-//
-// LDS swizzle.  The 16-byte chunk c of row r lives at chunk c ^ ((r ^ (r >> 3)) & 7): eight
-// consecutive rows (operand fetch, k-contiguous fill) and eight rows 8 apart (transposing
-// fill) both spread over all eight chunk positions, so neither side bank-conflicts.
+// Staging.  Operand tiles go HBM -> LDS directly (buffer loads with LDS destination): no
+// staging registers, no ds_write instructions, and the buffer descriptor's range check
+// zero-fills rows or k beyond the operand's edge without a branch.  NSTAGE LDS buffers rotate;
+// one barrier per K step.  K-contiguous tiles are read with ds_read_b128, k-major tiles with
+// the LDS transposing read (ds_read_b64_tr_b16), which delivers the MFMA operand order
+// straight from the [k][row] image.
 //
 // The grid is one-dimensional; tile ids are regrouped so that the workgroups that land on
 // one XCD (id mod 8) work on neighbouring tiles and share their operands in that XCD's L2.
@@ -34,11 +29,7 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
 
-constexpr int BK = 64;           // K step, bf16 elements
-constexpr int ROWB = BK * 2;     // bytes per LDS row
 constexpr uint32_t kOob = 0x80000000u;  // byte offset beyond every operand: the buffer load returns 0
-
-__device__ inline int swz(int row, int chunk) { return row * ROWB + ((chunk ^ ((row ^ (row >> 3)) & 7)) << 4); }
 
 // Raw buffer descriptor over [base, base+bytes): loads past the end return zero, so tile
 // edges need no branches (the range check covers the VGPR offset; the scalar offset is
@@ -46,83 +37,6 @@ __device__ inline int swz(int row, int chunk) { return row * ROWB + ((chunk ^ ((
 __device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes) {
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
 }
-
-// 8x8 transpose of 16-bit elements: in[r] holds row r (8 elements), out[c] column c.
-__device__ inline void transpose8x8(const u32x4 (&in)[8], u32x4 (&out)[8]) {
-#pragma unroll
-  for (int w = 0; w < 4; ++w)      // source dword = columns 2w, 2w+1
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {  // row pair 2p, 2p+1 -> destination dword p
-      const uint32_t a = in[2 * p][w], b = in[2 * p + 1][w];
-      out[2 * w][p] = (a & 0xFFFFu) | (b << 16);
-      out[2 * w + 1][p] = (a >> 16) | (b & 0xFFFF0000u);
-    }
-}
-
-// One operand tile of ROWS rows x 64 k.  A k-contiguous tile is fetched by all NT threads
-// of the workgroup; a k-major tile by the ROWS threads [T0, T0+ROWS), one 8x8 block each.
-template <int ROWS, bool KMAJOR, int NT, int T0>
-struct TileLoader {
-  static constexpr int NCH = KMAJOR ? 8 : ROWS * 8 / NT;  // 16-byte registers per thread
-  static_assert(KMAJOR || (ROWS * 8) % NT == 0, "tile rows must divide over the threads");
-  static_assert(!KMAJOR || T0 + ROWS <= NT, "not enough threads for the k-major tile");
-  struct Regs { u32x4 r[NCH]; };
-  uint32_t voff[NCH];  // byte offset of each load at k = 0 (kOob where the row is outside the operand)
-  int kofs;            // this thread's k offset inside the 64-wide step (first of its loads)
-  uint32_t kstride;    // bytes per unit of k
-
-  __device__ static inline bool mine(int t) { return !KMAJOR || (t >= T0 && t < T0 + ROWS); }
-
-  __device__ inline void init(int row0, int rows, int ld, int t) {
-    if constexpr (!KMAJOR) {
-      kofs = (t & 7) * 8;
-      kstride = 2;
-#pragma unroll
-      for (int i = 0; i < NCH; ++i) {
-        const int row = row0 + ((t + NT * i) >> 3);
-        voff[i] = row < rows ? ((uint32_t)row * ld + kofs) * 2u : kOob;
-      }
-    } else {
-      const int u = t - T0;
-      const int mb = u % (ROWS / 8), kb = u / (ROWS / 8);
-      const bool on = mine(t) && (row0 + mb * 8 < rows);
-      kofs = kb * 8;
-      kstride = (uint32_t)ld * 2u;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) voff[i] = on ? ((uint32_t)(kofs + i) * ld + row0 + mb * 8) * 2u : kOob;
-    }
-  }
-
-  // k0: first k of this step in operand coordinates; kend: bound on k
-  __device__ inline void fetch(Regs &x, __amdgpu_buffer_rsrc_t rs, int k0, int kend, int t) const {
-    if (!mine(t)) return;
-    const uint32_t adv = (uint32_t)k0 * kstride;
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      const bool ok = k0 + kofs + (KMAJOR ? i : 0) < kend;
-      x.r[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, ok ? voff[i] + adv : kOob, 0, 0);
-    }
-  }
-
-  __device__ inline void store(const Regs &x, char *lds, int t) const {
-    if constexpr (!KMAJOR) {
-#pragma unroll
-      for (int i = 0; i < NCH; ++i) {
-        const int c = t + NT * i;
-        *reinterpret_cast<u32x4 *>(lds + swz(c >> 3, c & 7)) = x.r[i];
-      }
-    } else {
-      if (mine(t)) {
-        const int u = t - T0;
-        const int mb = u % (ROWS / 8), kb = u / (ROWS / 8);
-        u32x4 o[8];
-        transpose8x8(x.r, o);
-#pragma unroll
-        for (int c = 0; c < 8; ++c) *reinterpret_cast<u32x4 *>(lds + swz(mb * 8 + c, kb)) = o[c];
-      }
-    }
-  }
-};
 
 __device__ inline void unpack8(const u32x4 v, float (&f)[8]) {
 #pragma unroll
@@ -222,126 +136,7 @@ __device__ inline void epilogue(const GemmArgs &g, floatx16 (&acc)[MI][NI], char
   }
 }
 
-template <int BM, int BN, int WGM, int WGN, int PF, bool AKM, bool BKM, int EPI>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_mfma_kernel(GemmArgs g) {
-  constexpr int NT = 64 * WGM * WGN;          // threads
-  constexpr int WTM = BM / WGM, WTN = BN / WGN;   // wavefront tile
-  constexpr int MI = WTM / 32, NI = WTN / 32; // MFMA tiles per wavefront
-  constexpr int STAGE = (BM + BN) * ROWB;
-  constexpr int SP = WTN + 4;                 // epilogue staging row pitch, floats
-  static_assert(WGM * WGN * 32 * SP * 4 <= 2 * STAGE, "epilogue staging must fit in the operand buffers");
-  __shared__ __attribute__((aligned(16))) char smem[2 * STAGE];
-
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int wm = wave / WGN, wn = wave % WGN;
-
-  // ---- tile id: XCD regrouping, then groups of 8 tile rows ----
-  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-  const int total = tiles_m * tiles_n;
-  int pid = blockIdx.x;
-  if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);
-  constexpr int GM = 8;
-  const int per_group = GM * tiles_n;
-  const int group = pid / per_group, first_m = group * GM;
-  const int gsize = min(tiles_m - first_m, GM);
-  const int tm = first_m + (pid % per_group) % gsize, tn = (pid % per_group) / gsize;
-  const int m0 = tm * BM, n0 = tn * BN;
-
-  const __amdgpu_buffer_rsrc_t ra = make_rsrc(g.A, g.a_bytes), rb = make_rsrc(g.B, g.b_bytes);
-  // when both tiles are k-major and there are threads to spare, different threads take A and B
-  constexpr int TB0 = (AKM && BKM && BM + BN <= NT) ? BM : 0;
-  TileLoader<BM, AKM, NT, 0> la;
-  TileLoader<BN, BKM, NT, TB0> lb;
-  la.init(m0, g.M, g.lda, t);
-  lb.init(n0, g.N, g.ldb, t);
-  const int nk = (g.K + BK - 1) / BK;
-  const bool seg = AKM && BKM && g.segs.nseg > 0;
-
-  typename TileLoader<BM, AKM, NT, 0>::Regs xa[PF];
-  typename TileLoader<BN, BKM, NT, TB0>::Regs xb[PF];
-  auto fetch = [&](int kt, int slot) {
-    int ka = kt * BK, kb = ka, kenda = g.K, kendb = g.K;
-    if (seg) {  // segmented reduction: a K step never straddles two segments
-      const int s = ka / g.seg_len, r = ka % g.seg_len;
-      ka = r; kenda = g.seg_len;
-      kb = g.segs.row0[s] + r; kendb = g.segs.row0[s] + g.seg_len;
-    }
-    la.fetch(xa[slot], ra, ka, kenda, t);
-    lb.fetch(xb[slot], rb, kb, kendb, t);
-  };
-
-  floatx16 acc[MI][NI];
-#pragma unroll
-  for (int i = 0; i < MI; ++i)
-#pragma unroll
-    for (int j = 0; j < NI; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  // Pipeline: PF K steps are in flight HBM -> registers at any time (enough bytes outstanding
-  // to cover the memory latency, which a single step of a small tile does not).  The tile for
-  // step kt+1 is written to the idle LDS buffer at the top of step kt, while step kt's MFMAs
-  // read the other buffer, and its registers are refilled with step kt+1+PF.  One barrier per
-  // step.  Step j+1 travels in register slot j % PF.
-  fetch(0, 0);
-  la.store(xa[0], smem, t);
-  lb.store(xb[0], smem + BM * ROWB, t);
-#pragma unroll
-  for (int sl = 0; sl < PF; ++sl)
-    if (1 + sl < nk) fetch(1 + sl, sl);
-  __syncthreads();
-
-  const int frow = lane & 31, fchunk = lane >> 5;
-  for (int kt0 = 0; kt0 < nk; kt0 += PF) {
-#pragma unroll
-   for (int sl = 0; sl < PF; ++sl) {
-    const int kt = kt0 + sl;
-    if (kt >= nk) break;
-    const char *sa = smem + (kt & 1) * STAGE;
-    const char *sb = sa + BM * ROWB;
-    if (kt + 1 < nk && !(g.tile & 16)) {
-      char *na = smem + ((kt + 1) & 1) * STAGE;
-      la.store(xa[sl], na, t);
-      lb.store(xb[sl], na + BM * ROWB, t);
-      if (kt + 1 + PF < nk) fetch(kt + 1 + PF, sl);
-    }
-    // operand fragments are fetched from LDS one 16-wide k slice ahead of the MFMAs that use them
-    bf16x8 af[2][MI], bfr[2][NI];
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-      af[0][i] = *reinterpret_cast<const bf16x8 *>(sa + swz(wm * WTM + i * 32 + frow, fchunk));
-#pragma unroll
-    for (int j = 0; j < NI; ++j)
-      bfr[0][j] = *reinterpret_cast<const bf16x8 *>(sb + swz(wn * WTN + j * 32 + frow, fchunk));
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      const int cur = ks & 1, nxt = cur ^ 1;
-      if (ks + 1 < BK / 16) {
-#pragma unroll
-        for (int i = 0; i < MI; ++i)
-          af[nxt][i] = *reinterpret_cast<const bf16x8 *>(sa + swz(wm * WTM + i * 32 + frow, 2 * (ks + 1) + fchunk));
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-          bfr[nxt][j] = *reinterpret_cast<const bf16x8 *>(sb + swz(wn * WTN + j * 32 + frow, 2 * (ks + 1) + fchunk));
-      }
-#pragma unroll
-      for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[cur][i], bfr[cur][j], acc[i][j], 0, 0, 0);
-    }
-    __syncthreads();
-   }
-  }
-
-  epilogue<BM, BN, WGM, WGN, EPI>(g, acc, smem, m0, n0, wave, lane);
-}
-
 // ------------------------------------------------------------------------------------------
-// Variant with direct HBM -> LDS operand staging (buffer loads with LDS destination) and,
-// for k-major operands, the LDS transposing read.  No staging registers, so NSTAGE LDS
-// buffers of BKT-wide K steps can be in flight.
-//
 // Direct loads write 16 bytes per lane at consecutive LDS addresses in lane order, so the
 // LDS image of a tile is fixed and the swizzle is applied on the global side: the thread that
 // fills LDS chunk position p fetches the logical chunk that belongs there.
@@ -518,38 +313,24 @@ hipError_t launch_dma(const GemmArgs &g, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int WGM, int WGN, int PF, bool AKM, bool BKM, int EPI>
-hipError_t launch(const GemmArgs &g, hipStream_t s) {
-  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
-  hipLaunchKernelGGL((gemm_mfma_kernel<BM, BN, WGM, WGN, PF, AKM, BKM, EPI>), dim3(tiles), dim3(64 * WGM * WGN), 0, s,
-                     g);
-  return hipGetLastError();
-}
-
 template <bool AKM, bool BKM, int EPI>
 hipError_t pick_tile(const GemmArgs &g, hipStream_t s) {
   auto tiles = [&](int bm, int bn) { return (long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn); };
-  switch (g.tile & 15) {
-    case 4: return launch_dma<256, 256, 2, 2, 64, 2, AKM, BKM, EPI>(g, s);
-    case 5: return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI>(g, s);
-    case 6: return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI>(g, s);
-    case 7: return launch_dma<256, 256, 2, 2, 32, 4, AKM, BKM, EPI>(g, s);
-    case 8: return launch_dma<256, 256, 2, 4, 32, 4, AKM, BKM, EPI>(g, s);
-    case 9: return launch_dma<128, 128, 2, 2, 32, 4, AKM, BKM, EPI>(g, s);
+  switch (g.tile) {
+    case 1: return launch_dma<256, 256, 2, 2, 64, 2, AKM, BKM, EPI>(g, s);
+    case 2: return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI>(g, s);
+    case 3: return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI>(g, s);
     default: break;
   }
-  if ((g.tile & 15) == 1) return launch<256, 256, 2, 2, 1, AKM, BKM, EPI>(g, s);
-  if ((g.tile & 15) == 2) return launch<256, 256, 2, 4, 1, AKM, BKM, EPI>(g, s);
-  if ((g.tile & 15) == 3) return launch<128, 128, 2, 2, 1, AKM, BKM, EPI>(g, s);
   // Measured on MI355X: with enough 256x256 tiles to cover most of the 256 CUs the large tile
-  // wins (8 wavefronts when no operand needs the transposing fill, 4 otherwise); below that
-  // the 128x128 tile, two workgroups per CU, keeps more CUs busy.
+  // wins (8 wavefronts; 4 when both operands take the transposing read); below that the
+  // 128x128 tile, two workgroups per CU, keeps more CUs busy.
   if (AKM && BKM) {
-    if (tiles(256, 256) >= 200) return launch<256, 256, 2, 2, 1, AKM, BKM, EPI>(g, s);
+    if (tiles(256, 256) >= 200) return launch_dma<256, 256, 2, 2, 64, 2, AKM, BKM, EPI>(g, s);
   } else if (tiles(256, 256) >= 160) {
-    return launch<256, 256, 2, 4, 1, AKM, BKM, EPI>(g, s);
+    return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI>(g, s);
   }
-  return launch<128, 128, 2, 2, 1, AKM, BKM, EPI>(g, s);
+  return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI>(g, s);
 }
 
 }  // namespace
@@ -577,7 +358,7 @@ hipError_t gemm_bf16(const GemmArgs &g0, hipStream_t s) {
   if (g.b_kmajor && (g.N & 7)) return hipErrorInvalidValue;
   if (!g.a_kmajor && (g.K & 7)) return hipErrorInvalidValue;
   if (!g.b_kmajor && (g.K & 7)) return hipErrorInvalidValue;
-  if (g.segs.nseg > 0 && (!g.a_kmajor || !g.b_kmajor || g.seg_len % BK || g.K != g.segs.nseg * g.seg_len))
+  if (g.segs.nseg > 0 && (!g.a_kmajor || !g.b_kmajor || g.seg_len % 64 || g.K != g.segs.nseg * g.seg_len))
     return hipErrorInvalidValue;
   const int lay = g.a_kmajor * 2 + g.b_kmajor;
   switch (lay) {
