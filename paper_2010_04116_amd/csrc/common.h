@@ -45,10 +45,6 @@ constexpr int kMaxStreams = 16;
 struct StreamWeights {
   float w[kMaxStreams];
 };
-struct SegList {  // streams that enter a weight gradient: starting row of each in the stack
-  int nseg;
-  int row0[kMaxStreams];
-};
 
 // ---- GEMM front ends (implemented in gemm_simt.hip / gemm_mfma.hip) ----------------
 enum Epi {
@@ -70,11 +66,6 @@ struct GemmArgs {
   int M, N, K;
   int lda, ldb;
   int a_kmajor, b_kmajor;
-  // When a_kmajor and segs.nseg > 0 the reduction runs over nseg segments of `seg_len`
-  // rows: B rows come from segs.row0[i] + r, A rows from r (the saved activation is
-  // shared by all streams).  K must equal nseg*seg_len.
-  SegList segs;
-  int seg_len;
   int epi;
   void *C;        // T or fp32 depending on epi
   void *C2;       // EPI_BIAS_GELU second output
@@ -106,9 +97,10 @@ int ln_backward_max_blocks();
 // ---- reductions / elementwise (reduce.hip) --------------------------------------------
 // out[c] = sum over blocks p of partials[p][c], c < cols (fp32 out, deterministic order)
 hipError_t colsum_final(const float *partials, int nblk, int cols, float *out, int accumulate, hipStream_t s);
-// partials[p][c] = sum over rows of block p of w(stream(row)) * Y[row][c]; returns nblk
-hipError_t colsum_partial(int dtype, const void *Y, int rows, int N, int cols, int ld, StreamWeights sw,
-                          float *partials, int *nblk, hipStream_t s);
+// ysum[r][c] = sum_s w[s] * Y[s*N + r][c] (stored in T when ysum != NULL, pitch = cols);
+// partials[p][c] = column sums of ysum over the rows of block p; returns nblk
+hipError_t sum_colsum(int dtype, const void *Y, int N, int cols, int ld, int ns, StreamWeights sw, void *ysum,
+                      float *partials, int *nblk, hipStream_t s);
 int colsum_max_blocks();
 // G[i] = (accumulate ? G[i] : 0) + src[i]; Gb[i] = T(G[i])
 hipError_t stream_inject(int dtype, const float *src, float *G, void *Gb, size_t count, int accumulate,

@@ -249,18 +249,10 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmArgs g) {
   lb.init(n0, g.N, g.ldb, t);
   constexpr int LPS = TA::NLD + TB::NLD;  // loads per thread per K step
   const int nk = (g.K + BKT - 1) / BKT;
-  const bool seg = AKM && BKM && g.segs.nseg > 0;
-
   auto issue = [&](int kt) {
     char *st = smem + (kt % NSTAGE) * STAGE;
-    int ka = kt * BKT, kb = ka, kenda = g.K, kendb = g.K;
-    if (seg) {
-      const int s = ka / g.seg_len, r = ka % g.seg_len;
-      ka = r; kenda = g.seg_len;
-      kb = g.segs.row0[s] + r; kendb = g.segs.row0[s] + g.seg_len;
-    }
-    la.issue(ra, st, wave, ka, kenda);
-    lb.issue(rb, st + ABYTES, wave, kb, kendb);
+    la.issue(ra, st, wave, kt * BKT, g.K);
+    lb.issue(rb, st + ABYTES, wave, kt * BKT, g.K);
   };
 
   floatx16 acc[MI][NI];
@@ -342,12 +334,8 @@ hipError_t gemm_bf16(const GemmArgs &g0, hipStream_t s) {
   if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
   if ((g.N & 7) || (g.ldc & 7) || ((uintptr_t)g.C & 15)) return hipErrorInvalidValue;
   {  // operand extents for the buffer descriptors (bytes, below 2 GiB)
-    size_t arows = g.a_kmajor ? (size_t)(g.segs.nseg > 0 ? g.seg_len : g.K) : (size_t)g.M;
-    size_t brows = g.b_kmajor ? (size_t)g.K : (size_t)g.N;
-    if (g.b_kmajor && g.segs.nseg > 0) {
-      brows = 0;
-      for (int i = 0; i < g.segs.nseg; ++i) brows = std::max(brows, (size_t)g.segs.row0[i] + g.seg_len);
-    }
+    const size_t arows = g.a_kmajor ? (size_t)g.K : (size_t)g.M;
+    const size_t brows = g.b_kmajor ? (size_t)g.K : (size_t)g.N;
     const size_t ab = arows * g.lda * 2, bb = brows * g.ldb * 2;
     if (ab >= 0x7FFFFFFFull || bb >= 0x7FFFFFFFull) return hipErrorInvalidValue;
     g.a_bytes = (uint32_t)ab;
@@ -358,8 +346,6 @@ hipError_t gemm_bf16(const GemmArgs &g0, hipStream_t s) {
   if (g.b_kmajor && (g.N & 7)) return hipErrorInvalidValue;
   if (!g.a_kmajor && (g.K & 7)) return hipErrorInvalidValue;
   if (!g.b_kmajor && (g.K & 7)) return hipErrorInvalidValue;
-  if (g.segs.nseg > 0 && (!g.a_kmajor || !g.b_kmajor || g.seg_len % 64 || g.K != g.segs.nseg * g.seg_len))
-    return hipErrorInvalidValue;
   const int lay = g.a_kmajor * 2 + g.b_kmajor;
   switch (lay) {
     case 1:  // activations x weights[K,N]: forward linears, head logits

@@ -1,7 +1,7 @@
 // Plain-FMA tiled GEMM with the library's fused epilogues.  This is the true-fp32
 // path (no matrix cores, no reduced-precision shortcuts) used when il_config.dtype is
 // IL_F32; sizes there are small, so the kernel favours generality over speed:
-// arbitrary M, N, K, both operand layouts, segmented reduction for weight gradients.
+// arbitrary M, N, K, both operand layouts.
 #include "common.h"
 
 namespace il {
@@ -30,8 +30,7 @@ __global__ __launch_bounds__(256) void gemm_simt_kernel(GemmArgs g) {
       float v = 0.f;
       if (gk < g.K && gm < g.M) {
         if (g.a_kmajor) {
-          int r = (g.segs.nseg > 0) ? gk % g.seg_len : gk;
-          v = ld<T>(A + (size_t)r * g.lda + gm);
+          v = ld<T>(A + (size_t)gk * g.lda + gm);
         } else {
           v = ld<T>(A + (size_t)gm * g.lda + gk);
         }
@@ -44,9 +43,7 @@ __global__ __launch_bounds__(256) void gemm_simt_kernel(GemmArgs g) {
       v = 0.f;
       if (gk < g.K && gn < g.N) {
         if (g.b_kmajor) {
-          int r = gk;
-          if (g.segs.nseg > 0) r = g.segs.row0[gk / g.seg_len] + gk % g.seg_len;
-          v = ld<T>(B + (size_t)r * g.ldb + gn);
+          v = ld<T>(B + (size_t)gk * g.ldb + gn);
         } else {
           v = ld<T>(B + (size_t)gn * g.ldb + gk);
         }

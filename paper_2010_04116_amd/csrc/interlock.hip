@@ -33,8 +33,9 @@ struct StreamDesc {
 struct Run {                    // a contiguous range of live slots, processed as one stack
   int s0 = 0, cnt = 0;          // slots [s0, s0+cnt)
   float wt[kMaxStreams] = {};   // routing weight of each stream at this component
-  SegList segs = {};            // streams with non-zero weight (stream index; times N at launch)
-  float wscale = 1.f;           // their common weight
+  int nweighted = 0;            // streams with non-zero weight
+  int first_weighted = -1;      // index of the first of them in the stack
+  float wscale = 1.f;           // weight of the last of them (used when there is exactly one)
   int acc = 0;                  // 1: parameter gradients add to what an earlier run wrote
 };
 struct CompPlan {
@@ -122,25 +123,19 @@ int build_plan(int K, int n, int route, Plan &p) {
         r.s0 = s;
         c.runs.push_back(r);
       }
-      Run &r = c.runs.back();
       const float wt = (float)W(k, p.streams[s].hi);
-      if (wt != 0.f && r.segs.nseg && wt != r.wscale) {  // one stack shares one weight-gradient scale
-        Run r2;
-        r2.s0 = s;
-        c.runs.push_back(r2);
-      }
       Run &q = c.runs.back();
       q.wt[q.cnt] = wt;
       if (wt != 0.f) {
         q.wscale = wt;
-        q.segs.row0[q.segs.nseg++] = q.cnt;
+        if (q.nweighted++ == 0) q.first_weighted = q.cnt;
       }
       ++q.cnt;
       ++c.cnt;
     }
     for (Run &r : c.runs) {
       p.maxcnt = std::max(p.maxcnt, r.cnt);
-      if (r.segs.nseg) { r.acc = written; written = true; }
+      if (r.nweighted) { r.acc = written; written = true; }
     }
     if (!written) return IL_E_ARG;  // a component no loss is credited to
     for (int j = k; j <= K; ++j)
@@ -179,7 +174,7 @@ struct il_ctx {
   std::vector<size_t> hoff;        // K
   std::vector<BlockSave> save;     // K*L
   float *G; char *Gb;              // stream slots [nslots][N,d]
-  char *DU, *DH, *DQKV; float *dsum, *partials;
+  char *DU, *DH, *DQKV, *YS; float *dsum, *partials;
   char *xb, *Z; float *rowloss, *dxh;
   int Nc;
   std::vector<char> fwd_done, head_done, bwd_done;
@@ -232,6 +227,7 @@ size_t layout_workspace(il_ctx *c, void *base) {
   c->DH = (char *)cv.take(S * d * eb);
   c->DQKV = (char *)cv.take(S * 3 * d * eb);
   c->dsum = (float *)cv.take(S * H * 4);
+  c->YS = (char *)cv.take(N * std::max((size_t)3 * d, m) * eb);
   size_t pcols = std::max((size_t)3 * d, m);
   size_t pbytes = std::max((size_t)ln_backward_max_blocks() * 2 * d, (size_t)colsum_max_blocks() * pcols) * 4;
   c->partials = (float *)cv.take(pbytes);
@@ -301,28 +297,35 @@ int linear_dgrad(il_ctx *c, const void *dy, size_t w_off, int M, int Kin, int No
   return IL_OK;
 }
 
-// dW[Kin,Nout] = scale * sum over included streams of x[N,Kin]^T dy_s[N,Nout];  db = weighted column sums
+// dW[Kin,Nout] = x[N,Kin]^T (sum_s w_s dy_s[N,Nout]);  db = column sums of the same weighted sum.
+// The streams are summed first (linearity of the weight gradient), fused with the first stage of
+// the bias-gradient column sum; one credited stream of weight 1 is used in place.
 int linear_wgrad(il_ctx *c, const Run &cp, const void *x, const void *dy, int Kin, int Nout, size_t w_off,
                  size_t b_off) {
-  if (cp.segs.nseg == 0) return IL_OK;  // pass-through streams only: nothing is credited
+  if (cp.nweighted == 0) return IL_OK;  // pass-through streams only: nothing is credited
+  const bool in_place = cp.nweighted == 1 && cp.wscale == 1.f;
+  const char *dys = in_place ? (const char *)dy + (size_t)cp.first_weighted * c->N * Nout * c->eb : c->YS;
+  {
+    StreamWeights sw;
+    memset(&sw, 0, sizeof(sw));
+    int nblk = 0;
+    Scope sc(c, KC_COLSUM, 0, (double)(in_place ? 1 : cp.nweighted + 1) * c->N * Nout * c->eb);
+    if (in_place) {
+      sw.w[0] = 1.f;
+      IL_TRY(sum_colsum(c->cfg.dtype, dys, c->N, Nout, Nout, 1, sw, nullptr, c->partials, &nblk, c->stream));
+    } else {
+      memcpy(sw.w, cp.wt, sizeof(sw.w));
+      IL_TRY(sum_colsum(c->cfg.dtype, dy, c->N, Nout, Nout, cp.cnt, sw, c->YS, c->partials, &nblk, c->stream));
+    }
+    IL_TRY(colsum_final(c->partials, nblk, Nout, Gr(c, b_off), cp.acc, c->stream));
+  }
   GemmArgs g = base_args();
   g.A = x; g.lda = Kin; g.a_kmajor = 1;
-  g.B = dy; g.ldb = Nout; g.b_kmajor = 1;
-  g.M = Kin; g.N = Nout; g.segs = cp.segs; g.seg_len = c->N;
-  for (int i = 0; i < g.segs.nseg; ++i) g.segs.row0[i] *= c->N;
-  g.K = g.segs.nseg * c->N;
-  g.epi = EPI_WGRAD; g.C = Gr(c, w_off); g.ldc = Nout; g.scale = cp.wscale; g.beta = cp.acc;
-  {
-    Scope sc(c, KC_GEMM_WGRAD, 2.0 * g.K * Kin * Nout, 0);
-    IL_TRY(gemm(c, g));
-  }
-  StreamWeights sw;
-  memcpy(sw.w, cp.wt, sizeof(sw.w));
-  int nblk = 0;
-  const int rows = cp.cnt * c->N;
-  Scope sc(c, KC_COLSUM, 0, (double)rows * Nout * c->eb);
-  IL_TRY(colsum_partial(c->cfg.dtype, dy, rows, c->N, Nout, Nout, sw, c->partials, &nblk, c->stream));
-  IL_TRY(colsum_final(c->partials, nblk, Nout, Gr(c, b_off), cp.acc, c->stream));
+  g.B = dys; g.ldb = Nout; g.b_kmajor = 1;
+  g.M = Kin; g.N = Nout; g.K = c->N;
+  g.epi = EPI_WGRAD; g.C = Gr(c, w_off); g.ldc = Nout; g.scale = 1.f; g.beta = cp.acc;
+  Scope sc(c, KC_GEMM_WGRAD, 2.0 * g.K * Kin * Nout, 0);
+  IL_TRY(gemm(c, g));
   return IL_OK;
 }
 
@@ -348,7 +351,7 @@ int ln_bwd(il_ctx *c, const Run &cp, const void *dy, const float *x, const float
   Scope sc(c, KC_LN_BWD, 0, (double)rows * c->d * (c->eb + 8 + c->eb) + (double)c->N * c->d * 4);
   IL_TRY(ln_backward_residual(c->cfg.dtype, dy, x, stats, P(c, g_off), rows, c->N, c->d, G, Gb, sw, c->partials,
                               &nblk, c->stream));
-  if (cp.segs.nseg) IL_TRY(colsum_final(c->partials, nblk, 2 * c->d, Gr(c, g_off), cp.acc, c->stream));
+  if (cp.nweighted) IL_TRY(colsum_final(c->partials, nblk, 2 * c->d, Gr(c, g_off), cp.acc, c->stream));
   return IL_OK;
 }
 

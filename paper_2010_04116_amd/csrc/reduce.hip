@@ -8,35 +8,59 @@ namespace {
 
 constexpr int kColBlocksY = 64;   // row splits of the first stage
 
-// First stage.  V = 8: grid (ceil(cols/256), nby), block = 32 column groups of 8 x 8 row
-// lanes, 16-byte loads (cols % 8 == 0).  V = 1: block = 64 columns x 4 row lanes.
+// First stage, fused with the weighted sum over gradient streams.  Y holds `ns` stacked
+// streams of N rows; for every token row the kernel forms ysum = sum_s w[s] * Y[s*N + row] in
+// fp32, optionally stores it (rounded to T) for the weight-gradient GEMM, and accumulates its
+// column sums (the bias gradient).  V = 8: grid (ceil(cols/256), nby), block = 32 column groups
+// of 8 x 8 row lanes, 16-byte accesses (cols % 8 == 0).  V = 1: block = 64 columns x 4 row lanes.
 template <typename T, int V>
-__global__ __launch_bounds__(256) void colsum_partial_kernel(const T *__restrict__ Y, int rows, int N, int cols,
-                                                             int ldy, StreamWeights sw,
-                                                             float *__restrict__ partials) {
+__global__ __launch_bounds__(256) void sum_colsum_kernel(const T *__restrict__ Y, int N, int cols, int ldy, int ns,
+                                                         StreamWeights sw, T *__restrict__ ysum,
+                                                         float *__restrict__ partials) {
   constexpr int CG = V == 8 ? 32 : 64, RL = 256 / CG;
   __shared__ float red[RL][CG * V];
   const int tx = threadIdx.x % CG, ty = threadIdx.x / CG;
   const int c = (blockIdx.x * CG + tx) * V;
-  const int per = (rows + gridDim.y - 1) / gridDim.y;
-  const int r0 = blockIdx.y * per, r1 = min(rows, r0 + per);
+  const int per = (N + gridDim.y - 1) / gridDim.y;
+  const int r0 = blockIdx.y * per, r1 = min(N, r0 + per);
   float acc[V];
 #pragma unroll
   for (int e = 0; e < V; ++e) acc[e] = 0.f;
   if (c < cols)
     for (int r = r0 + ty; r < r1; r += RL) {
-      const float w = sw.w[r / N];
-      if constexpr (V == 8) {
-        const uint4 v = *reinterpret_cast<const uint4 *>(Y + (size_t)r * ldy + c);
-        const uint32_t u[4] = {v.x, v.y, v.z, v.w};
+      float v[V];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          acc[2 * e] += w * bf16_to_f32((bf16_t)(u[e] & 0xFFFF));
-          acc[2 * e + 1] += w * bf16_to_f32((bf16_t)(u[e] >> 16));
+      for (int e = 0; e < V; ++e) v[e] = 0.f;
+      for (int si = 0; si < ns; ++si) {
+        const float w = sw.w[si];
+        if (w == 0.f) continue;
+        const T *src = Y + ((size_t)si * N + r) * ldy + c;
+        if constexpr (V == 8) {
+          const uint4 q = *reinterpret_cast<const uint4 *>(src);
+          const uint32_t u[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            v[2 * e] += w * bf16_to_f32((bf16_t)(u[e] & 0xFFFF));
+            v[2 * e + 1] += w * bf16_to_f32((bf16_t)(u[e] >> 16));
+          }
+        } else {
+          v[0] += w * ld<T>(src);
         }
-      } else {
-        acc[0] += w * ld<T>(Y + (size_t)r * ldy + c);
       }
+      if (ysum) {
+        if constexpr (V == 8) {
+          uint4 q;
+          q.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+          q.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+          q.z = (uint32_t)f32_to_bf16(v[4]) | ((uint32_t)f32_to_bf16(v[5]) << 16);
+          q.w = (uint32_t)f32_to_bf16(v[6]) | ((uint32_t)f32_to_bf16(v[7]) << 16);
+          *reinterpret_cast<uint4 *>(ysum + (size_t)r * cols + c) = q;
+        } else {
+          st<T>(ysum + (size_t)r * cols + c, v[0]);
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < V; ++e) acc[e] += v[e];
     }
 #pragma unroll
   for (int e = 0; e < V; ++e) red[ty][tx * V + e] = acc[e];
@@ -126,21 +150,21 @@ inline int grid_for(size_t count) {
 
 int colsum_max_blocks() { return kColBlocksY; }
 
-hipError_t colsum_partial(int dtype, const void *Y, int rows, int N, int cols, int ldy, StreamWeights sw,
-                          float *partials, int *nblk, hipStream_t s) {
-  int nby = (rows + 63) / 64;
+hipError_t sum_colsum(int dtype, const void *Y, int N, int cols, int ldy, int ns, StreamWeights sw, void *ysum,
+                      float *partials, int *nblk, hipStream_t s) {
+  int nby = (N + 63) / 64;
   if (nby > kColBlocksY) nby = kColBlocksY;
   if (nby < 1) nby = 1;
   *nblk = nby;
   if (dtype == 0)
-    hipLaunchKernelGGL((colsum_partial_kernel<float, 1>), dim3((cols + 63) / 64, nby), dim3(256), 0, s,
-                       (const float *)Y, rows, N, cols, ldy, sw, partials);
+    hipLaunchKernelGGL((sum_colsum_kernel<float, 1>), dim3((cols + 63) / 64, nby), dim3(256), 0, s,
+                       (const float *)Y, N, cols, ldy, ns, sw, (float *)ysum, partials);
   else if ((cols & 7) == 0 && (ldy & 7) == 0)
-    hipLaunchKernelGGL((colsum_partial_kernel<bf16_t, 8>), dim3((cols + 255) / 256, nby), dim3(256), 0, s,
-                       (const bf16_t *)Y, rows, N, cols, ldy, sw, partials);
+    hipLaunchKernelGGL((sum_colsum_kernel<bf16_t, 8>), dim3((cols + 255) / 256, nby), dim3(256), 0, s,
+                       (const bf16_t *)Y, N, cols, ldy, ns, sw, (bf16_t *)ysum, partials);
   else
-    hipLaunchKernelGGL((colsum_partial_kernel<bf16_t, 1>), dim3((cols + 63) / 64, nby), dim3(256), 0, s,
-                       (const bf16_t *)Y, rows, N, cols, ldy, sw, partials);
+    hipLaunchKernelGGL((sum_colsum_kernel<bf16_t, 1>), dim3((cols + 63) / 64, nby), dim3(256), 0, s,
+                       (const bf16_t *)Y, N, cols, ldy, ns, sw, (bf16_t *)ysum, partials);
   return hipGetLastError();
 }
 
