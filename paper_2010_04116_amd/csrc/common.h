@@ -76,12 +76,24 @@ struct GemmArgs {
   int aux_wrap;       // rows of aux (row index taken modulo this)
   float scale;        // EPI_WGRAD
   uint32_t a_bytes, b_bytes;  // operand extents in bytes (filled by the bf16 front end)
+  int k_begin, k_end; // reduction range [k_begin, k_end); both 0 = all of K (used by split-K)
   int tile;           // bf16: 0 = choose by shape, 1 = 256x256/4 waves, 2 = 256x256/8 waves, 3 = 128x128
   int beta;           // EPI_WGRAD: accumulate into C
 };
 
 hipError_t gemm_f32(const GemmArgs &g, hipStream_t s);    // T = float, SIMT
 hipError_t gemm_bf16(const GemmArgs &g, hipStream_t s);   // T = bf16, MFMA
+// Up to kMaxBatch independent GEMMs with the same operand layouts and epilogue in ONE launch
+// (their tiles share the grid, so small problems fill the chip together).
+constexpr int kMaxBatch = 8;
+hipError_t gemm_bf16_batch(const GemmArgs *list, int count, hipStream_t s);
+// Split-K for fp32-output epilogues (EPI_STORE_F32, EPI_WGRAD): `splits` partial products over
+// disjoint K ranges go to ws ([splits][M][N] fp32) in one launch, then a reduction applies the
+// epilogue.  Deterministic (fixed summation order).
+hipError_t gemm_bf16_splitk(const GemmArgs &g, int splits, float *ws, hipStream_t s);
+// out[i] = scale * sum_p part[p*stride + i] (+ out[i] if beta), rows x cols with pitch ldc
+hipError_t splitk_reduce(const float *part, int splits, size_t stride, int rows, int cols, float *out, int ldc,
+                         float scale, int beta, hipStream_t s);
 
 // ---- row-wise kernels (layernorm.hip) -----------------------------------------------
 // y = LN(x)*gamma+beta -> T; stats[row] = (mean, rstd); optional fp32 copy of x.

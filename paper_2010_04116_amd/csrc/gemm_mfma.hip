@@ -19,6 +19,7 @@
 // The grid is one-dimensional; tile ids are regrouped so that the workgroups that land on
 // one XCD (id mod 8) work on neighbouring tiles and share their operands in that XCD's L2.
 #include <algorithm>
+#include <cstring>
 
 #include "common.h"
 
@@ -215,8 +216,14 @@ struct DmaTile {
 
 constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
+struct GemmBatch {
+  int count;
+  int tile_end[kMaxBatch];  // exclusive prefix of tile counts
+  GemmArgs p[kMaxBatch];
+};
+
 template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGE, bool AKM, bool BKM, int EPI>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmArgs g) {
+__global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmBatch batch) {
   constexpr int NT = 64 * WGM * WGN;
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int MI = WTM / 32, NI = WTN / 32;
@@ -229,9 +236,14 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmArgs g) {
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int wm = wave / WGN, wn = wave % WGN;
 
+  // which problem of the batch this workgroup belongs to (uniform)
+  int prob = 0, tile0 = 0;
+  for (int i = 0; i < batch.count - 1; ++i)
+    if ((int)blockIdx.x >= batch.tile_end[i]) { prob = i + 1; tile0 = batch.tile_end[i]; }
+  const GemmArgs &g = batch.p[prob];
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   const int total = tiles_m * tiles_n;
-  int pid = blockIdx.x;
+  int pid = blockIdx.x - tile0;
   if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);
   constexpr int GM = 8;
   const int per_group = GM * tiles_n;
@@ -248,11 +260,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmArgs g) {
   la.init(m0, g.M, g.lda, t);
   lb.init(n0, g.N, g.ldb, t);
   constexpr int LPS = TA::NLD + TB::NLD;  // loads per thread per K step
-  const int nk = (g.K + BKT - 1) / BKT;
+  const int kb0 = g.k_end > 0 ? g.k_begin : 0, ke = g.k_end > 0 ? g.k_end : g.K;
+  const int nk = (ke - kb0 + BKT - 1) / BKT;
   auto issue = [&](int kt) {
     char *st = smem + (kt % NSTAGE) * STAGE;
-    la.issue(ra, st, wave, kt * BKT, g.K);
-    lb.issue(rb, st + ABYTES, wave, kt * BKT, g.K);
+    la.issue(ra, st, wave, kb0 + kt * BKT, ke);
+    lb.issue(rb, st + ABYTES, wave, kb0 + kt * BKT, ke);
   };
 
   floatx16 acc[MI][NI];
@@ -298,76 +311,153 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmArgs g) {
 }
 
 template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGE, bool AKM, bool BKM, int EPI>
-hipError_t launch_dma(const GemmArgs &g, hipStream_t s) {
-  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+hipError_t launch_dma(GemmBatch &b, hipStream_t s) {
+  int tiles = 0;
+  for (int i = 0; i < b.count; ++i) {
+    tiles += ((b.p[i].M + BM - 1) / BM) * ((b.p[i].N + BN - 1) / BN);
+    b.tile_end[i] = tiles;
+  }
   hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, BKT, NSTAGE, AKM, BKM, EPI>), dim3(tiles),
-                     dim3(64 * WGM * WGN), 0, s, g);
+                     dim3(64 * WGM * WGN), 0, s, b);
   return hipGetLastError();
 }
 
 template <bool AKM, bool BKM, int EPI>
-hipError_t pick_tile(const GemmArgs &g, hipStream_t s) {
-  auto tiles = [&](int bm, int bn) { return (long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn); };
-  switch (g.tile) {
-    case 1: return launch_dma<256, 256, 2, 2, 64, 2, AKM, BKM, EPI>(g, s);
-    case 2: return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI>(g, s);
-    case 3: return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI>(g, s);
+hipError_t pick_tile(GemmBatch &b, hipStream_t s) {
+  long t256 = 0;
+  for (int i = 0; i < b.count; ++i) t256 += (long)((b.p[i].M + 255) / 256) * ((b.p[i].N + 255) / 256);
+  switch (b.p[0].tile) {
+    case 1: return launch_dma<256, 256, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
+    case 2: return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI>(b, s);
+    case 3: return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
     default: break;
   }
   // Measured on MI355X: with enough 256x256 tiles to cover most of the 256 CUs the large tile
   // wins (8 wavefronts; 4 when both operands take the transposing read); below that the
   // 128x128 tile, two workgroups per CU, keeps more CUs busy.
   if (AKM && BKM) {
-    if (tiles(256, 256) >= 200) return launch_dma<256, 256, 2, 2, 64, 2, AKM, BKM, EPI>(g, s);
-  } else if (tiles(256, 256) >= 160) {
-    return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI>(g, s);
+    if (t256 >= 200) return launch_dma<256, 256, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
+  } else if (t256 >= 160) {
+    return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI>(b, s);
   }
-  return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI>(g, s);
+  return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
+}
+
+// argument checks and buffer extents of one problem
+hipError_t prepare(GemmArgs &g) {
+  if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
+  if ((g.N & 7) || (g.ldc & 7) || ((uintptr_t)g.C & 15)) return hipErrorInvalidValue;
+  if ((g.lda & 7) || (g.ldb & 7) || ((uintptr_t)g.A & 15) || ((uintptr_t)g.B & 15)) return hipErrorInvalidValue;
+  if (g.a_kmajor && (g.M & 7)) return hipErrorInvalidValue;
+  if (g.b_kmajor && (g.N & 7)) return hipErrorInvalidValue;
+  if (!g.a_kmajor && (g.K & 7)) return hipErrorInvalidValue;
+  if (!g.b_kmajor && (g.K & 7)) return hipErrorInvalidValue;
+  if (g.k_end < 0 || g.k_begin < 0 || g.k_end > g.K || (g.k_end > 0 && g.k_begin >= g.k_end) || (g.k_begin & 7) ||
+      (g.k_end & 7))
+    return hipErrorInvalidValue;
+  const size_t arows = g.a_kmajor ? (size_t)g.K : (size_t)g.M;
+  const size_t brows = g.b_kmajor ? (size_t)g.K : (size_t)g.N;
+  const size_t ab = arows * g.lda * 2, bb = brows * g.ldb * 2;  // bytes, below 2 GiB
+  if (ab >= 0x7FFFFFFFull || bb >= 0x7FFFFFFFull) return hipErrorInvalidValue;
+  g.a_bytes = (uint32_t)ab;
+  g.b_bytes = (uint32_t)bb;
+  return hipSuccess;
+}
+
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ part, int splits, size_t stride,
+                                                            int rows, int cols, float *out, int ldc, float scale,
+                                                            int beta) {
+  const int c4 = cols >> 2;
+  const size_t total = (size_t)rows * c4;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+    const int r = (int)(i / c4), c = (int)(i % c4) * 4;
+    float4 a = *reinterpret_cast<const float4 *>(part + (size_t)r * cols + c);
+    for (int p = 1; p < splits; ++p) {
+      const float4 b = *reinterpret_cast<const float4 *>(part + p * stride + (size_t)r * cols + c);
+      a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    float *o = out + (size_t)r * ldc + c;
+    a.x *= scale; a.y *= scale; a.z *= scale; a.w *= scale;
+    if (beta) {
+      const float4 b = *reinterpret_cast<const float4 *>(o);
+      a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+    }
+    *reinterpret_cast<float4 *>(o) = a;
+  }
 }
 
 }  // namespace
 
 // The step uses exactly these (layout, epilogue) combinations; anything else is a
 // programming error in the caller and is reported instead of silently taking another path.
-hipError_t gemm_bf16(const GemmArgs &g0, hipStream_t s) {
-  GemmArgs g = g0;
-  if (g.M <= 0 || g.N <= 0 || g.K <= 0) return hipErrorInvalidValue;
-  if ((g.N & 7) || (g.ldc & 7) || ((uintptr_t)g.C & 15)) return hipErrorInvalidValue;
-  {  // operand extents for the buffer descriptors (bytes, below 2 GiB)
-    const size_t arows = g.a_kmajor ? (size_t)g.K : (size_t)g.M;
-    const size_t brows = g.b_kmajor ? (size_t)g.K : (size_t)g.N;
-    const size_t ab = arows * g.lda * 2, bb = brows * g.ldb * 2;
-    if (ab >= 0x7FFFFFFFull || bb >= 0x7FFFFFFFull) return hipErrorInvalidValue;
-    g.a_bytes = (uint32_t)ab;
-    g.b_bytes = (uint32_t)bb;
+hipError_t gemm_bf16_batch(const GemmArgs *list, int count, hipStream_t s) {
+  if (count < 1 || count > kMaxBatch) return hipErrorInvalidValue;
+  GemmBatch b;
+  memset(&b, 0, sizeof(b));
+  b.count = count;
+  for (int i = 0; i < count; ++i) {
+    b.p[i] = list[i];
+    if (list[i].a_kmajor != list[0].a_kmajor || list[i].b_kmajor != list[0].b_kmajor || list[i].epi != list[0].epi)
+      return hipErrorInvalidValue;
+    const hipError_t e = prepare(b.p[i]);
+    if (e != hipSuccess) return e;
   }
-  if ((g.lda & 7) || (g.ldb & 7) || ((uintptr_t)g.A & 15) || ((uintptr_t)g.B & 15)) return hipErrorInvalidValue;
-  if (g.a_kmajor && (g.M & 7)) return hipErrorInvalidValue;
-  if (g.b_kmajor && (g.N & 7)) return hipErrorInvalidValue;
-  if (!g.a_kmajor && (g.K & 7)) return hipErrorInvalidValue;
-  if (!g.b_kmajor && (g.K & 7)) return hipErrorInvalidValue;
+  const GemmArgs &g = b.p[0];
   const int lay = g.a_kmajor * 2 + g.b_kmajor;
   switch (lay) {
     case 1:  // activations x weights[K,N]: forward linears, head logits
       switch (g.epi) {
-        case EPI_STORE: return pick_tile<false, true, EPI_STORE>(g, s);
-        case EPI_BIAS: return pick_tile<false, true, EPI_BIAS>(g, s);
-        case EPI_BIAS_GELU: return pick_tile<false, true, EPI_BIAS_GELU>(g, s);
-        case EPI_BIAS_RES: return pick_tile<false, true, EPI_BIAS_RES>(g, s);
+        case EPI_STORE: return pick_tile<false, true, EPI_STORE>(b, s);
+        case EPI_BIAS: return pick_tile<false, true, EPI_BIAS>(b, s);
+        case EPI_BIAS_GELU: return pick_tile<false, true, EPI_BIAS_GELU>(b, s);
+        case EPI_BIAS_RES: return pick_tile<false, true, EPI_BIAS_RES>(b, s);
         default: return hipErrorInvalidValue;
       }
     case 0:  // dY x W^T with W stored [N,K]: data gradients
       switch (g.epi) {
-        case EPI_STORE: return pick_tile<false, false, EPI_STORE>(g, s);
-        case EPI_GELU_BWD: return pick_tile<false, false, EPI_GELU_BWD>(g, s);
-        case EPI_STORE_F32: return pick_tile<false, false, EPI_STORE_F32>(g, s);
+        case EPI_STORE: return pick_tile<false, false, EPI_STORE>(b, s);
+        case EPI_GELU_BWD: return pick_tile<false, false, EPI_GELU_BWD>(b, s);
+        case EPI_STORE_F32: return pick_tile<false, false, EPI_STORE_F32>(b, s);
         default: return hipErrorInvalidValue;
       }
     case 3:  // X^T dY: weight gradients
-      if (g.epi == EPI_WGRAD) return pick_tile<true, true, EPI_WGRAD>(g, s);
+      if (g.epi == EPI_WGRAD) return pick_tile<true, true, EPI_WGRAD>(b, s);
       return hipErrorInvalidValue;
     default: return hipErrorInvalidValue;
   }
+}
+
+hipError_t gemm_bf16(const GemmArgs &g, hipStream_t s) { return gemm_bf16_batch(&g, 1, s); }
+
+hipError_t splitk_reduce(const float *part, int splits, size_t stride, int rows, int cols, float *out, int ldc,
+                         float scale, int beta, hipStream_t s) {
+  if ((cols & 3) || (ldc & 3)) return hipErrorInvalidValue;
+  size_t blocks = ((size_t)rows * (cols >> 2) + 255) / 256;
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, s, part, splits, stride, rows, cols,
+                     out, ldc, scale, beta);
+  return hipGetLastError();
+}
+
+hipError_t gemm_bf16_splitk(const GemmArgs &g, int splits, float *ws, hipStream_t s) {
+  if (splits < 2 || splits > kMaxBatch || !ws) return hipErrorInvalidValue;
+  if (g.epi != EPI_STORE_F32 && g.epi != EPI_WGRAD) return hipErrorInvalidValue;
+  GemmArgs list[kMaxBatch];
+  const int steps = (g.K + 63) / 64, per = (steps + splits - 1) / splits;
+  int n = 0;
+  for (int i = 0; i < splits; ++i) {
+    const int k0 = i * per * 64, k1 = std::min(g.K, (i + 1) * per * 64);
+    if (k0 >= k1) break;
+    list[n] = g;
+    list[n].k_begin = k0; list[n].k_end = k1;
+    list[n].C = ws + (size_t)n * g.M * g.N; list[n].ldc = g.N;
+    list[n].scale = 1.f; list[n].beta = 0;
+    ++n;
+  }
+  hipError_t e = gemm_bf16_batch(list, n, s);
+  if (e != hipSuccess) return e;
+  return splitk_reduce(ws, n, (size_t)g.M * g.N, g.M, g.N, (float *)g.C, g.ldc, g.epi == EPI_WGRAD ? g.scale : 1.f,
+                       g.epi == EPI_WGRAD ? g.beta : 0, s);
 }
 
 }  // namespace il

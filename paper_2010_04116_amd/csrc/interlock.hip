@@ -174,7 +174,7 @@ struct il_ctx {
   std::vector<size_t> hoff;        // K
   std::vector<BlockSave> save;     // K*L
   float *G; char *Gb;              // stream slots [nslots][N,d]
-  char *DU, *DH, *DQKV, *YS; float *dsum, *partials;
+  char *DU, *DH, *DQKV, *YS[4]; float *dsum, *partials, *skws; size_t skws_floats;
   char *xb, *Z; float *rowloss, *dxh;
   int Nc;
   std::vector<char> fwd_done, head_done, bwd_done;
@@ -227,7 +227,12 @@ size_t layout_workspace(il_ctx *c, void *base) {
   c->DH = (char *)cv.take(S * d * eb);
   c->DQKV = (char *)cv.take(S * 3 * d * eb);
   c->dsum = (float *)cv.take(S * H * 4);
-  c->YS = (char *)cv.take(N * std::max((size_t)3 * d, m) * eb);
+  c->YS[0] = (char *)cv.take(N * d * eb);      // summed dY of FC2
+  c->YS[1] = (char *)cv.take(N * m * eb);      // FC1
+  c->YS[2] = (char *)cv.take(N * d * eb);      // attention output projection
+  c->YS[3] = (char *)cv.take(N * 3 * d * eb);  // QKV
+  c->skws_floats = (size_t)kMaxBatch * c->Nc * d;
+  c->skws = (float *)cv.take(c->skws_floats * 4);
   size_t pcols = std::max((size_t)3 * d, m);
   size_t pbytes = std::max((size_t)ln_backward_max_blocks() * 2 * d, (size_t)colsum_max_blocks() * pcols) * 4;
   c->partials = (float *)cv.take(pbytes);
@@ -299,12 +304,15 @@ int linear_dgrad(il_ctx *c, const void *dy, size_t w_off, int M, int Kin, int No
 
 // dW[Kin,Nout] = x[N,Kin]^T (sum_s w_s dy_s[N,Nout]);  db = column sums of the same weighted sum.
 // The streams are summed first (linearity of the weight gradient), fused with the first stage of
-// the bias-gradient column sum; one credited stream of weight 1 is used in place.
+// the bias-gradient column sum.  The GEMM itself is only described here (`out`); the four weight
+// gradients of a block are launched together at the end of the block's backward so that their
+// tiles share one grid.  `keep`: dy is overwritten before then, so the sum must be materialised
+// even for a single stream of weight 1.
 int linear_wgrad(il_ctx *c, const Run &cp, const void *x, const void *dy, int Kin, int Nout, size_t w_off,
-                 size_t b_off) {
+                 size_t b_off, int slot, bool keep, GemmArgs *out, int *nout) {
   if (cp.nweighted == 0) return IL_OK;  // pass-through streams only: nothing is credited
-  const bool in_place = cp.nweighted == 1 && cp.wscale == 1.f;
-  const char *dys = in_place ? (const char *)dy + (size_t)cp.first_weighted * c->N * Nout * c->eb : c->YS;
+  const bool in_place = cp.nweighted == 1 && cp.wscale == 1.f && !keep;
+  const char *dys = in_place ? (const char *)dy + (size_t)cp.first_weighted * c->N * Nout * c->eb : c->YS[slot];
   {
     StreamWeights sw;
     memset(&sw, 0, sizeof(sw));
@@ -315,7 +323,8 @@ int linear_wgrad(il_ctx *c, const Run &cp, const void *x, const void *dy, int Ki
       IL_TRY(sum_colsum(c->cfg.dtype, dys, c->N, Nout, Nout, 1, sw, nullptr, c->partials, &nblk, c->stream));
     } else {
       memcpy(sw.w, cp.wt, sizeof(sw.w));
-      IL_TRY(sum_colsum(c->cfg.dtype, dy, c->N, Nout, Nout, cp.cnt, sw, c->YS, c->partials, &nblk, c->stream));
+      IL_TRY(sum_colsum(c->cfg.dtype, dy, c->N, Nout, Nout, cp.cnt, sw, c->YS[slot], c->partials, &nblk,
+                        c->stream));
     }
     IL_TRY(colsum_final(c->partials, nblk, Nout, Gr(c, b_off), cp.acc, c->stream));
   }
@@ -324,9 +333,32 @@ int linear_wgrad(il_ctx *c, const Run &cp, const void *x, const void *dy, int Ki
   g.B = dys; g.ldb = Nout; g.b_kmajor = 1;
   g.M = Kin; g.N = Nout; g.K = c->N;
   g.epi = EPI_WGRAD; g.C = Gr(c, w_off); g.ldc = Nout; g.scale = 1.f; g.beta = cp.acc;
-  Scope sc(c, KC_GEMM_WGRAD, 2.0 * g.K * Kin * Nout, 0);
-  IL_TRY(gemm(c, g));
+  out[(*nout)++] = g;
   return IL_OK;
+}
+
+int launch_wgrads(il_ctx *c, const GemmArgs *list, int n) {
+  if (n == 0) return IL_OK;
+  double fl = 0;
+  for (int i = 0; i < n; ++i) fl += 2.0 * list[i].M * list[i].N * list[i].K;
+  Scope sc(c, KC_GEMM_WGRAD, fl, 0);
+  if (c->cfg.dtype == IL_F32) {
+    for (int i = 0; i < n; ++i) IL_TRY(gemm_f32(list[i], c->stream));
+  } else {
+    IL_TRY(gemm_bf16_batch(list, n, c->stream));
+  }
+  return IL_OK;
+}
+
+// Split-K factor for an fp32-output GEMM whose 128x128 tiles alone would leave CUs idle.
+int choose_splits(il_ctx *c, int M, int N, int K) {
+  const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
+  if (c->cfg.dtype != IL_BF16 || tiles >= 200) return 1;
+  long sp = 512 / tiles;
+  sp = std::min<long>(sp, kMaxBatch);
+  sp = std::min<long>(sp, K / 1024);
+  sp = std::min<long>(sp, (long)(c->skws_floats / ((size_t)M * N)));
+  return sp < 2 ? 1 : (int)sp;
 }
 
 int attention_fwd(il_ctx *c, const void *qkv, void *o, float *lse) {
@@ -380,21 +412,22 @@ int block_backward(il_ctx *c, const Run &cp, const BlockOff &b, const BlockSave 
   const int S = cp.cnt * N;
   float *G = c->G + (size_t)cp.s0 * N * d;
   char *Gb = c->Gb + (size_t)cp.s0 * N * d * c->eb;
-  int rc;
+  int rc, nw = 0;
+  GemmArgs wg[4];
   // MLP
   if ((rc = linear_dgrad(c, Gb, b.w_fc2, S, m, d, EPI_GELU_BWD, c->DU, s.u, N))) return rc;
-  if ((rc = linear_wgrad(c, cp, s.gl, Gb, m, d, b.w_fc2, b.b_fc2))) return rc;
-  if ((rc = linear_wgrad(c, cp, s.h2, c->DU, d, m, b.w_fc1, b.b_fc1))) return rc;
+  if ((rc = linear_wgrad(c, cp, s.gl, Gb, m, d, b.w_fc2, b.b_fc2, 0, true, wg, &nw))) return rc;
+  if ((rc = linear_wgrad(c, cp, s.h2, c->DU, d, m, b.w_fc1, b.b_fc1, 1, false, wg, &nw))) return rc;
   if ((rc = linear_dgrad(c, c->DU, b.w_fc1, S, d, m, EPI_STORE, c->DH, nullptr, 0))) return rc;
   if ((rc = ln_bwd(c, cp, c->DH, s.a, s.st2, b.ln2_g, G, Gb))) return rc;
   // attention
-  if ((rc = linear_wgrad(c, cp, s.o, Gb, d, d, b.w_o, b.b_o))) return rc;
+  if ((rc = linear_wgrad(c, cp, s.o, Gb, d, d, b.w_o, b.b_o, 2, true, wg, &nw))) return rc;
   if ((rc = linear_dgrad(c, Gb, b.w_o, S, d, d, EPI_STORE, c->DH, nullptr, 0))) return rc;
   if ((rc = attention_bwd(c, s, c->DH, cp.cnt, c->DQKV))) return rc;
-  if ((rc = linear_wgrad(c, cp, s.h1, c->DQKV, d, 3 * d, b.w_qkv, b.b_qkv))) return rc;
+  if ((rc = linear_wgrad(c, cp, s.h1, c->DQKV, d, 3 * d, b.w_qkv, b.b_qkv, 3, false, wg, &nw))) return rc;
   if ((rc = linear_dgrad(c, c->DQKV, b.w_qkv, S, d, 3 * d, EPI_STORE, c->DH, nullptr, 0))) return rc;
   if ((rc = ln_bwd(c, cp, c->DH, s.xs, s.st1, b.ln1_g, G, Gb))) return rc;
-  return IL_OK;
+  return launch_wgrads(c, wg, nw);
 }
 
 int validate(const il_config *cfg) {
@@ -542,7 +575,9 @@ int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets,
     g.M = rows; g.N = d; g.K = V; g.epi = EPI_STORE_F32; g.C = dx + (size_t)r0 * d; g.ldc = d;
     {
       Scope sc(c, KC_GEMM_HEAD, 2.0 * rows * V * d, 0);
-      IL_TRY(gemm(c, g));
+      const int sp = choose_splits(c, rows, d, V);
+      if (sp > 1) IL_TRY(gemm_bf16_splitk(g, sp, c->skws, c->stream));
+      else IL_TRY(gemm(c, g));
     }
     g = base_args();  // dW_h (+)= x^T dz
     g.A = xc; g.lda = d; g.a_kmajor = 1;
