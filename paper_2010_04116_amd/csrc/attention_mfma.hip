@@ -1,6 +1,6 @@
 // Causal attention forward / backward on the gfx950 matrix cores for bf16 and head
-// widths 64 and 128.  K/V (forward, dQ) or Q/dO (dK, dV) tiles are LDS-resident and double
-// buffered; scores are never written to memory.
+// widths 64 and 128.  K/V (forward, dQ) or Q/dO (dK, dV) tiles are LDS-resident, double
+// buffered and filled by direct HBM -> LDS loads; scores are never written to memory.
 //
 // Orientation.  Scores are computed transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16:
 // a lane then owns ONE query column (lane & 31) and holds 16 key rows per 32x32 tile in its
@@ -9,7 +9,8 @@
 // accumulators into the B operand of the second product O^T = V^T P^T without touching LDS:
 // the MFMA's k index is only a summation label, so the key order a lane happens to hold
 // (rows 4h..4h+3 and 8+4h..8+4h+3 of each 16-key group, h = lane >> 5) is used as is and the
-// A operand (V^T, staged transposed in LDS) is read in the same order.
+// A operand V^T is fetched in the same order from the [key][dh] tile with the LDS transposing
+// read (each source lane may point at any row, so no transposed copy is staged).
 //
 // The backward recomputes the probabilities from the saved log-sum-exp in two kernels with
 // fixed reduction order (no atomics): one owns a key/value tile and accumulates dK, dV over
@@ -21,30 +22,15 @@ namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4v;
+typedef __attribute__((address_space(3))) void lds_void;
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kNegBig = -1.0e30f;
+constexpr uint32_t kOob = 0x80000000u;  // byte offset past every buffer: the load returns 0
 
-// byte offset of 16-byte chunk `chunk` of row `row` in an LDS tile with `rowb` bytes per row
-__device__ inline int swz(int row, int chunk, int rowb) {
-  return row * rowb + ((chunk ^ ((row ^ (row >> 3)) & 7)) << 4);
-}
 __device__ inline uint4 ldg16(const bf16_t *p) { return *reinterpret_cast<const uint4 *>(p); }
-
-__device__ inline void transpose8x8(const uint4 (&in)[8], uint4 (&out)[8]) {
-  const uint32_t *s = reinterpret_cast<const uint32_t *>(in);
-  uint32_t *o = reinterpret_cast<uint32_t *>(out);
-#pragma unroll
-  for (int w = 0; w < 4; ++w)
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      uint32_t a = s[(2 * p) * 4 + w], b = s[(2 * p + 1) * 4 + w];
-      o[(2 * w) * 4 + p] = (a & 0xFFFFu) | (b << 16);
-      o[(2 * w + 1) * 4 + p] = (a >> 16) | (b & 0xFFFF0000u);
-    }
-}
-
 __device__ inline uint32_t pack2(float a, float b) {
   return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
 }
@@ -53,73 +39,71 @@ union Frag {
   uint4 q;
   uint2 h[2];
   uint32_t u[4];
+  short4v s[2];
 };
-
-// A [ROWS x DH] tile of rows `row0..` of a token-major matrix (row stride ld), staged as is
-// ([row][dh], dh contiguous).  Rows >= row_end are zero.
-template <int ROWS, int DH>
-struct RowTile {
-  static constexpr int NCH = ROWS * DH / 8 / 256;
-  static_assert(NCH >= 1, "tile too small for 256 threads");
-  uint4 r[NCH];
-  __device__ inline void fetch(const bf16_t *base, size_t ld, int row0, int row_end, int t) {
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      const int c = t + 256 * i, row = c / (DH / 8), ch = c % (DH / 8);
-      r[i] = (row0 + row < row_end) ? ldg16(base + (size_t)(row0 + row) * ld + ch * 8) : make_uint4(0, 0, 0, 0);
-    }
-  }
-  __device__ inline void store(char *lds, int t) const {
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      const int c = t + 256 * i, row = c / (DH / 8), ch = c % (DH / 8);
-      *reinterpret_cast<uint4 *>(lds + swz(row, ch, DH * 2)) = r[i];
-    }
-  }
-};
-
-// The same [ROWS x DH] tile staged transposed: LDS row = dh index, ROWS token columns.
-template <int ROWS, int DH>
-struct ColTile {
-  static constexpr int NBLK = (ROWS / 8) * (DH / 8);  // 8x8 blocks
-  static constexpr int PER = (NBLK + 255) / 256;
-  uint4 r[PER][8];
-  __device__ inline void fetch(const bf16_t *base, size_t ld, int row0, int row_end, int t) {
-#pragma unroll
-    for (int j = 0; j < PER; ++j) {
-      const int blk = t + 256 * j;
-      const int db = blk % (DH / 8), rb = blk / (DH / 8);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int row = row0 + rb * 8 + i;
-        r[j][i] = (blk < NBLK && row < row_end) ? ldg16(base + (size_t)row * ld + db * 8) : make_uint4(0, 0, 0, 0);
-      }
-    }
-  }
-  __device__ inline void store(char *lds, int t) const {
-#pragma unroll
-    for (int j = 0; j < PER; ++j) {
-      const int blk = t + 256 * j;
-      if (blk < NBLK) {
-        const int db = blk % (DH / 8), rb = blk / (DH / 8);
-        uint4 o[8];
-        transpose8x8(r[j], o);
-#pragma unroll
-        for (int c = 0; c < 8; ++c) *reinterpret_cast<uint4 *>(lds + swz(db * 8 + c, rb, ROWS * 2)) = o[c];
-      }
-    }
-  }
-};
-
-// MFMA A operand for a product whose k index runs over 16 token columns of a transposed
-// tile, in the order a lane holds them in a 32x32 accumulator: columns c0*8 + 4h + (0..3) and
-// c0*8 + 8 + 4h + (0..3).
-__device__ inline bf16x8 read_tr_frag(const char *lds, int row, int c0, int hh, int rowb) {
-  Frag f;
-  f.h[0] = *reinterpret_cast<const uint2 *>(lds + swz(row, c0, rowb) + 8 * hh);
-  f.h[1] = *reinterpret_cast<const uint2 *>(lds + swz(row, c0 + 1, rowb) + 8 * hh);
-  return f.v;
+__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *base, size_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
 }
+constexpr int vmcnt0_imm() { return (7 << 4) | (15 << 8); }
+
+// A [ROWS tokens] x [DH] tile of a token-major matrix, staged as is ([token][dh]) by direct
+// loads (256 threads, 16 bytes each per round).  The 16-byte chunk c of row r sits at chunk
+// position c ^ h(r), h(r) = ((r & 3) << 1) | ((r >> 2) & 1): eight consecutive rows spread over
+// eight positions (row fragments, ds_read_b128) and four consecutive rows over four position
+// pairs (transposing reads of 32 bytes per row), so neither access bank-conflicts.
+template <int ROWS, int DH>
+struct TokTile {
+  static constexpr int RB = DH * 2, CPR = DH / 8, BYTES = ROWS * RB, NLD = BYTES / (256 * 16);
+  static_assert(BYTES % (256 * 16) == 0 && NLD >= 1, "tile must divide over 256 threads");
+  uint32_t voff[NLD];
+  int radd[NLD];
+  uint32_t rstride;
+  __device__ static inline int h(int r) { return ((r & 3) << 1) | ((r >> 2) & 1); }
+  // col0: first element column of this head; ld: elements per token row
+  __device__ inline void init(int col0, int ld, int t) {
+    rstride = (uint32_t)ld * 2u;
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int p = i * 256 + t, row = p / CPR, chunk = (p % CPR) ^ h(row);
+      radd[i] = row;
+      voff[i] = ((uint32_t)row * ld + col0 + chunk * 8) * 2u;
+    }
+  }
+  // rows [row0, row0 + ROWS) of the matrix; rows >= row_end read as zero
+  __device__ inline void issue(__amdgpu_buffer_rsrc_t rs, char *lds, int wave, int row0, int row_end) const {
+    const uint32_t adv = (uint32_t)row0 * rstride;
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const bool ok = row0 + radd[i] < row_end;
+#if defined(__HIP_DEVICE_COMPILE__)  // the host pass cannot type-check this builtin
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(lds + (i * 256 + wave * 64) * 16), 16,
+                                               ok ? voff[i] + adv : kOob, 0, 0, 0);
+#else
+      (void)rs; (void)lds; (void)wave; (void)ok; (void)adv;
+#endif
+    }
+  }
+  // MFMA operand with the tile's rows as matrix rows and dh as k: rows rbase + (lane & 31),
+  // dh slice [16 ks, 16 ks + 16)
+  __device__ static inline bf16x8 rowfrag(const char *lds, int rbase, int ks, int lane) {
+    const int row = rbase + (lane & 31), chunk = 2 * ks + (lane >> 5);
+    return *reinterpret_cast<const bf16x8 *>(lds + row * RB + ((chunk ^ h(row)) << 4));
+  }
+  // MFMA A operand with dh as matrix rows (dt*32 + (lane & 31)) and 16 tokens as k, in the
+  // order a lane holds them in a 32x32 accumulator: tokens tok0 + 4h + (0..3), tok0 + 8 + 4h + (0..3).
+  __device__ static inline bf16x8 trfrag(const char *lds, int tok0, int dt, int lane) {
+    const int g16 = lane >> 4, i = lane & 15;
+    const int dcol = dt * 32 + 16 * (g16 & 1) + 4 * (i & 3);
+    const int row = tok0 + 4 * (g16 >> 1) + (i >> 2);
+    const int sub = ((dcol >> 2) & 1) * 8;
+    Frag f;
+    f.s[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)(
+        lds + row * RB + (((dcol >> 3) ^ h(row)) << 4) + sub));
+    f.s[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v *)(
+        lds + (row + 8) * RB + (((dcol >> 3) ^ h(row + 8)) << 4) + sub));
+    return f.v;
+  }
+};
 
 // ------------------------------------------------------------------ forward -------------
 // grid (ceil(T/128), B*H); 4 wavefronts, each owns 32 queries; key tiles of 64.
@@ -127,9 +111,11 @@ template <int DH>
 __global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16_t *__restrict__ qkv, int T, int H,
                                                      bf16_t *__restrict__ o, float *__restrict__ lse) {
   constexpr int BQ = 128, BKV = 64;
-  constexpr int KT = BKV * DH * 2, VT = DH * BKV * 2, STAGE = KT + VT;
+  constexpr int KT = BKV * DH * 2, STAGE = 2 * KT;
+  typedef TokTile<BKV, DH> Tile;
   __shared__ __attribute__((aligned(16))) char smem[2 * STAGE];
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6, hh = lane >> 5, lq = lane & 31;
+  const int t = threadIdx.x, lane = t & 63, hh = lane >> 5, lq = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int qt = gridDim.x - 1 - blockIdx.x;  // long rows first
   const int b = blockIdx.y / H, h = blockIdx.y % H;
   const int d = H * DH;
@@ -153,20 +139,22 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16_t *__restrict__ 
   float m = kNegBig, l = 0.f;
   const float sc = rsqrtf((float)DH) * kLog2e;
 
-  RowTile<BKV, DH> lk;
-  ColTile<BKV, DH> lv;
-  lk.fetch(kbase, ld3, 0, T, t);
-  lv.fetch(vbase, ld3, 0, T, t);
-  lk.store(smem, t);
-  lv.store(smem + KT, t);
-  __syncthreads();
+  const __amdgpu_buffer_rsrc_t rs = make_rsrc(qbase, (size_t)T * ld3 * 2 - (size_t)h * DH * 2);
+  Tile lk, lv;
+  lk.init(d, (int)ld3, t);
+  lv.init(2 * d, (int)ld3, t);
+  lk.issue(rs, smem, wave, 0, T);
+  lv.issue(rs, smem + KT, wave, 0, T);
 
   for (int kt = 0; kt < nkv; ++kt) {
     const char *sk = smem + (kt & 1) * STAGE, *sv = sk + KT;
     const int kv0 = kt * BKV;
+    __builtin_amdgcn_s_waitcnt(vmcnt0_imm());
+    __syncthreads();  // tile kt is complete; every wavefront is done with tile kt-1
     if (kt + 1 < nkv) {
-      lk.fetch(kbase, ld3, kv0 + BKV, T, t);
-      lv.fetch(vbase, ld3, kv0 + BKV, T, t);
+      char *nk = smem + ((kt + 1) & 1) * STAGE;
+      lk.issue(rs, nk, wave, kv0 + BKV, T);
+      lv.issue(rs, nk + KT, wave, kv0 + BKV, T);
     }
     if (kv0 <= qw0 + 31) {  // some key of the tile is visible to some query of this wavefront
       floatx16 s[2];
@@ -176,7 +164,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16_t *__restrict__ 
         for (int r = 0; r < 16; ++r) s[a][r] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < DH / 16; ++ks) {
-          const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(sk + swz(32 * a + lq, 2 * ks + hh, DH * 2));
+          const bf16x8 kf = Tile::rowfrag(sk, 32 * a, ks, lane);
           s[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks].v, s[a], 0, 0, 0);
         }
       }
@@ -221,17 +209,11 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16_t *__restrict__ 
           for (int e = 0; e < 4; ++e) pf.u[e] = pack2(s[a][8 * bq + 2 * e], s[a][8 * bq + 2 * e + 1]);
 #pragma unroll
           for (int dt = 0; dt < DH / 32; ++dt) {
-            const bf16x8 vf = read_tr_frag(sv, dt * 32 + lq, 4 * a + 2 * bq, hh, BKV * 2);
+            const bf16x8 vf = Tile::trfrag(sv, 32 * a + 16 * bq, dt, lane);
             oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf.v, oacc[dt], 0, 0, 0);
           }
         }
     }
-    if (kt + 1 < nkv) {
-      char *nk = smem + ((kt + 1) & 1) * STAGE;
-      lk.store(nk, t);
-      lv.store(nk + KT, t);
-    }
-    __syncthreads();
   }
 
   l += __shfl_xor(l, 32, 64);
@@ -261,9 +243,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t *__restrict
                                                         const float *__restrict__ lse, int B, int T, int H,
                                                         bf16_t *__restrict__ dqkv, float *__restrict__ dsum) {
   constexpr int BQ = 128, BKV = 64;
-  constexpr int KT = BKV * DH * 2, STAGE = 3 * KT;  // K, V as stored, K transposed
+  constexpr int KT = BKV * DH * 2, STAGE = 2 * KT;  // K and V tiles as stored
+  typedef TokTile<BKV, DH> Tile;
   __shared__ __attribute__((aligned(16))) char smem[2 * STAGE];
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6, hh = lane >> 5, lq = lane & 31;
+  const int t = threadIdx.x, lane = t & 63, hh = lane >> 5, lq = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int qt = gridDim.x - 1 - blockIdx.x;
   const int b = blockIdx.y / H, h = blockIdx.y % H, sidx = blockIdx.z;
   const int d = H * DH;
@@ -308,23 +292,22 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t *__restrict
 #pragma unroll
     for (int r = 0; r < 16; ++r) dq[i][r] = 0.f;
 
-  RowTile<BKV, DH> lk, lv;
-  ColTile<BKV, DH> lkt;
-  lk.fetch(kbase, ld3, 0, T, t);
-  lv.fetch(vbase, ld3, 0, T, t);
-  lkt.fetch(kbase, ld3, 0, T, t);
-  lk.store(smem, t);
-  lv.store(smem + KT, t);
-  lkt.store(smem + 2 * KT, t);
-  __syncthreads();
+  const __amdgpu_buffer_rsrc_t rs = make_rsrc(qbase, (size_t)T * ld3 * 2 - (size_t)h * DH * 2);
+  Tile lk, lv;
+  lk.init(d, (int)ld3, t);
+  lv.init(2 * d, (int)ld3, t);
+  lk.issue(rs, smem, wave, 0, T);
+  lv.issue(rs, smem + KT, wave, 0, T);
 
   for (int kt = 0; kt < nkv; ++kt) {
-    const char *sk = smem + (kt & 1) * STAGE, *sv = sk + KT, *skt = sk + 2 * KT;
+    const char *sk = smem + (kt & 1) * STAGE, *sv = sk + KT;
     const int kv0 = kt * BKV;
+    __builtin_amdgcn_s_waitcnt(vmcnt0_imm());
+    __syncthreads();
     if (kt + 1 < nkv) {
-      lk.fetch(kbase, ld3, kv0 + BKV, T, t);
-      lv.fetch(vbase, ld3, kv0 + BKV, T, t);
-      lkt.fetch(kbase, ld3, kv0 + BKV, T, t);
+      char *nk = smem + ((kt + 1) & 1) * STAGE;
+      lk.issue(rs, nk, wave, kv0 + BKV, T);
+      lv.issue(rs, nk + KT, wave, kv0 + BKV, T);
     }
     if (kv0 <= qw0 + 31) {
       const bool diag = kv0 + BKV - 1 > qw0 || kv0 + BKV > T;
@@ -335,8 +318,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t *__restrict
         for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
         for (int ks = 0; ks < DH / 16; ++ks) {
-          const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(sk + swz(32 * a + lq, 2 * ks + hh, DH * 2));
-          const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(sv + swz(32 * a + lq, 2 * ks + hh, DH * 2));
+          const bf16x8 kf = Tile::rowfrag(sk, 32 * a, ks, lane);
+          const bf16x8 vf = Tile::rowfrag(sv, 32 * a, ks, lane);
           s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks].v, s, 0, 0, 0);
           dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, gf[ks].v, dp, 0, 0, 0);
         }
@@ -356,19 +339,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t *__restrict
           for (int e = 0; e < 4; ++e) pf.u[e] = pack2(s[8 * bq + 2 * e], s[8 * bq + 2 * e + 1]);
 #pragma unroll
           for (int dt = 0; dt < DH / 32; ++dt) {
-            const bf16x8 kf = read_tr_frag(skt, dt * 32 + lq, 4 * a + 2 * bq, hh, BKV * 2);
+            const bf16x8 kf = Tile::trfrag(sk, 32 * a + 16 * bq, dt, lane);
             dq[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, pf.v, dq[dt], 0, 0, 0);
           }
         }
       }
     }
-    if (kt + 1 < nkv) {
-      char *nk = smem + ((kt + 1) & 1) * STAGE;
-      lk.store(nk, t);
-      lv.store(nk + KT, t);
-      lkt.store(nk + 2 * KT, t);
-    }
-    __syncthreads();
   }
   if (q < T) {
     bf16_t *op = dqkv + (sidx * N + tok) * ld3 + h * DH;
@@ -397,9 +373,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t *__restric
                                                          bf16_t *__restrict__ dqkv) {
   constexpr int BKV = 128, BQ = 64;
   constexpr int QT = BQ * DH * 2;                 // one staged tile
-  constexpr int STAGE = 4 * QT + 2 * BQ * 4;      // Q, dO, Q^T, dO^T, lse, dsum
+  constexpr int STAGE = 2 * QT + 2 * BQ * 4;      // Q, dO as stored, lse, dsum
+  typedef TokTile<BQ, DH> Tile;
   __shared__ __attribute__((aligned(16))) char smem[2 * STAGE];
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6, hh = lane >> 5, lk_ = lane & 31;
+  const int t = threadIdx.x, lane = t & 63, hh = lane >> 5, lk_ = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
   const int b = blockIdx.y / H, h = blockIdx.y % H, sidx = blockIdx.z;
   const int d = H * DH;
   const size_t ld3 = 3 * (size_t)d, N = (size_t)B * T;
@@ -430,43 +408,34 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t *__restric
   const float sc = rsqrtf((float)DH);
   const float sc2 = sc * kLog2e;
 
-  RowTile<BQ, DH> lq, lg;
-  ColTile<BQ, DH> lqt, lgt;
-  float pl = 0.f, pd = 0.f;  // lse / dsum prefetch (threads 0..63)
-  auto fetch = [&](int qt) {
+  const __amdgpu_buffer_rsrc_t rq = make_rsrc(qbase, (size_t)T * ld3 * 2 - (size_t)h * DH * 2);
+  const __amdgpu_buffer_rsrc_t rg = make_rsrc(gbase, (size_t)T * d * 2 - (size_t)h * DH * 2);
+  Tile lq, lg;
+  lq.init(0, (int)ld3, t);
+  lg.init(0, d, t);
+  const __amdgpu_buffer_rsrc_t rl = make_rsrc(lrow, (size_t)T * 4), rd = make_rsrc(drow, (size_t)T * 4);
+  auto issue = [&](int qt, char *base) {  // direct loads of the Q and dO tiles and of 64 lse / dsum values
     const int r0 = qt * BQ;
-    lq.fetch(qbase, ld3, r0, T, t);
-    lg.fetch(gbase, d, r0, T, t);
-    lqt.fetch(qbase, ld3, r0, T, t);
-    lgt.fetch(gbase, d, r0, T, t);
-    if (t < BQ) {
-      const bool in = r0 + t < T;
-      pl = in ? lrow[r0 + t] * kLog2e : 0.f;
-      pd = in ? drow[r0 + t] : 0.f;
-    }
+    lq.issue(rq, base, wave, r0, T);
+    lg.issue(rg, base + QT, wave, r0, T);
+#if defined(__HIP_DEVICE_COMPILE__)
+    if (wave == 0)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rl, (lds_void *)(base + 2 * QT), 4, (uint32_t)(r0 + lane) * 4u, 0, 0, 0);
+    if (wave == 1)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rd, (lds_void *)(base + 2 * QT + BQ * 4), 4,
+                                               (uint32_t)(r0 + lane) * 4u, 0, 0, 0);
+#endif
   };
-  auto stage = [&](char *base) {
-    lq.store(base, t);
-    lg.store(base + QT, t);
-    lqt.store(base + 2 * QT, t);
-    lgt.store(base + 3 * QT, t);
-    if (t < BQ) {
-      reinterpret_cast<float *>(base + 4 * QT)[t] = pl;
-      reinterpret_cast<float *>(base + 4 * QT + BQ * 4)[t] = pd;
-    }
-  };
-  if (qt0 < nqt) {
-    fetch(qt0);
-    stage(smem);
-  }
-  __syncthreads();
+  if (qt0 < nqt) issue(qt0, smem);
 
   for (int qt = qt0; qt < nqt; ++qt) {
     const int it = qt - qt0;
-    const char *sq = smem + (it & 1) * STAGE, *sg = sq + QT, *sqt = sq + 2 * QT, *sgt = sq + 3 * QT;
-    const float *sl = reinterpret_cast<const float *>(sq + 4 * QT), *sd = sl + BQ;
+    const char *sq = smem + (it & 1) * STAGE, *sg = sq + QT;
+    const float *sl = reinterpret_cast<const float *>(sq + 2 * QT), *sd = sl + BQ;
     const int qb0 = qt * BQ;
-    if (qt + 1 < nqt) fetch(qt + 1);
+    __builtin_amdgcn_s_waitcnt(vmcnt0_imm());
+    __syncthreads();
+    if (qt + 1 < nqt) issue(qt + 1, smem + ((it + 1) & 1) * STAGE);
 #pragma unroll
     for (int a = 0; a < BQ / 32; ++a) {
       const int qa0 = qb0 + 32 * a;
@@ -476,8 +445,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t *__restric
       for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < DH / 16; ++ks) {
-        const bf16x8 qf = *reinterpret_cast<const bf16x8 *>(sq + swz(32 * a + lk_, 2 * ks + hh, DH * 2));
-        const bf16x8 gf = *reinterpret_cast<const bf16x8 *>(sg + swz(32 * a + lk_, 2 * ks + hh, DH * 2));
+        const bf16x8 qf = Tile::rowfrag(sq, 32 * a, ks, lane);
+        const bf16x8 gf = Tile::rowfrag(sg, 32 * a, ks, lane);
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[ks].v, s, 0, 0, 0);
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf, vf[ks].v, dp, 0, 0, 0);
       }
@@ -491,7 +460,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t *__restric
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = 4 * g + e;
-          float p = exp2f(s[r] * sc2 - lv4[e]);
+          float p = exp2f(s[r] * sc2 - lv4[e] * kLog2e);
           if (diag) {
             const int qq = qa0 + 8 * g + 4 * hh + e;
             if (kv > qq || qq >= T) p = 0.f;
@@ -510,15 +479,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t *__restric
         }
 #pragma unroll
         for (int dt = 0; dt < DH / 32; ++dt) {
-          const bf16x8 gt = read_tr_frag(sgt, dt * 32 + lk_, 4 * a + 2 * bq, hh, BQ * 2);
-          const bf16x8 qtf = read_tr_frag(sqt, dt * 32 + lk_, 4 * a + 2 * bq, hh, BQ * 2);
+          const bf16x8 gt = Tile::trfrag(sg, 32 * a + 16 * bq, dt, lane);
+          const bf16x8 qtf = Tile::trfrag(sq, 32 * a + 16 * bq, dt, lane);
           dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, pf.v, dv[dt], 0, 0, 0);
           dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qtf, sf.v, dk[dt], 0, 0, 0);
         }
       }
     }
-    if (qt + 1 < nqt) stage(smem + ((it + 1) & 1) * STAGE);
-    __syncthreads();
   }
   if (kv < T) {
     bf16_t *kp = dqkv + (sidx * N + (size_t)b * T + kv) * ld3 + d + h * DH;
