@@ -229,8 +229,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmBatch batc
   constexpr int MI = WTM / 32, NI = WTN / 32;
   constexpr int ABYTES = BM * BKT * 2, STAGE = (BM + BN) * BKT * 2;
   constexpr int SP = WTN + 4;
-  static_assert(WGM * WGN * 32 * SP * 4 <= NSTAGE * STAGE, "epilogue staging must fit in the operand buffers");
-  __shared__ __attribute__((aligned(16))) char smem[NSTAGE * STAGE];
+  constexpr int EPIB = WGM * WGN * 32 * SP * 4;  // epilogue staging reuses the operand buffers
+  __shared__ __attribute__((aligned(16))) char smem[NSTAGE * STAGE > EPIB ? NSTAGE * STAGE : EPIB];
 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
