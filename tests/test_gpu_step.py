@@ -144,3 +144,48 @@ def test_large_shape_one_component_and_head():
     say("case large slice K=1 L=1")
     got, ref = run_both(w, seed=8, random_ln=False)
     say("worst", compare(w, got, ref, "large slice"))
+
+
+# ------------------------------------------------ full-size workloads, sampled -------
+
+def _sampled_full_size(name, seed):
+    """The workload exactly as bench.py runs it (all components, heads, routing, tile and
+    chunk choices).  Sequences are independent, so the oracle run on sequence 0 alone fixes
+    (a) every x_k row of that sequence and (b) dL/dx_0 of that sequence: the batch mean over
+    B*T positions makes the full-batch value 1/B of the single-sequence one."""
+    from oracle import interlock as O
+    w = synth.WORKLOADS[name]
+    params = synth.make_params(w, synth.PARAM_SEED + seed)
+    inp, tgt = synth.make_tokens(w, synth.TOKEN_SEED + seed)
+    x0 = synth.make_x0(w, inp, synth.PARAM_SEED + seed)
+    say("case full-size", name, "GPU step")
+    got = binding.run_step(w, params, x0, tgt)
+    say("oracle on sequence 0")
+    ref = O.nwise_streams(params, x0[:w.T].astype(np.float64), tgt[:1], 1, w.T, w.H, w.n)
+    comps, heads, xs, *_ = O.forward_all(params, x0[:w.T].astype(np.float64), tgt[:1], 1, w.T, w.H)
+    for k in range(w.K):
+        e = np.linalg.norm(got["x"][k + 1][:w.T] - xs[k]) / np.linalg.norm(xs[k])
+        assert e <= 1e-2, f"{name}: x_{k + 1} rows of sequence 0: rel err {e:.3e}"
+    e = np.linalg.norm(got["dx0"][:w.T] * w.B - ref["dx0"]) / np.linalg.norm(ref["dx0"])
+    say("dx0 rel err", e)
+    assert e <= 2e-2, f"{name}: dL/dx_0 of sequence 0: rel err {e:.3e}"
+    # whole-batch properties: every loss is at least ln V minus noise; gradients are finite and non-zero
+    assert np.all(np.isfinite(got["losses"])) and np.all(got["losses"] > np.log(w.V) - 0.5)
+    for k in range(w.K):
+        for name_ in ("w_qkv", "w_fc2", "ln1_g", "b_fc1"):
+            g = got["comp_grads"][k][w.L - 1][name_]
+            assert np.all(np.isfinite(g)) and np.linalg.norm(g) > 0
+        assert np.all(np.isfinite(got["head_grads"][k]))
+        np.testing.assert_allclose(got["head_grads"][k].sum(axis=1), 0, atol=2e-3)   # sum_v dlogits = 0
+
+
+def test_medium_full_size_sampled():
+    _sampled_full_size("medium", 11)
+
+
+def test_many_head_full_size_sampled():
+    _sampled_full_size("many_head", 12)
+
+
+def test_large_full_size_sampled():
+    _sampled_full_size("large", 13)
