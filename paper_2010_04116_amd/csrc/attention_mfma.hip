@@ -32,7 +32,7 @@ constexpr uint32_t kOob = 0x80000000u;  // byte offset past every buffer: the lo
 
 __device__ inline uint4 ldg16(const bf16_t *p) { return *reinterpret_cast<const uint4 *>(p); }
 __device__ inline uint32_t pack2(float a, float b) {
-  return (uint32_t)f32_to_bf16(a) | ((uint32_t)f32_to_bf16(b) << 16);
+  return pack_bf16x2(a, b);
 }
 union Frag {
   bf16x8 v;

@@ -12,12 +12,27 @@ __host__ __device__ inline float bf16_to_f32(bf16_t h) {
   c.u = ((uint32_t)h) << 16;
   return c.f;
 }
-__host__ __device__ inline bf16_t f32_to_bf16(float f) {  // round to nearest even
+// float -> bfloat16, round to nearest even.  On the device this is the hardware conversion
+// (v_cvt_pk_bf16_f32); the host version does the same rounding in integer arithmetic.
+__host__ __device__ inline bf16_t f32_to_bf16(float f) {
+#if defined(__HIP_DEVICE_COMPILE__)
+  const __bf16 b = (__bf16)f;
+  return __builtin_bit_cast(bf16_t, b);
+#else
   union { uint32_t u; float f; } c;
   c.f = f;
   uint32_t u = c.u;
   u += 0x7FFFu + ((u >> 16) & 1u);
   return (bf16_t)(u >> 16);
+#endif
+}
+// two floats -> packed bf16 pair (a in the low half)
+__device__ inline uint32_t pack_bf16x2(float a, float b) {
+  typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
+  bf16x2_t v;
+  v[0] = (__bf16)a;
+  v[1] = (__bf16)b;
+  return __builtin_bit_cast(uint32_t, v);
 }
 
 template <typename T> __device__ inline float ld(const T *p);
@@ -110,7 +125,14 @@ int ln_backward_max_blocks();
 // out[c] = sum over blocks p of partials[p][c], c < cols (fp32 out, deterministic order)
 hipError_t colsum_final(const float *partials, int nblk, int cols, float *out, int accumulate, hipStream_t s);
 // ysum[r][c] = sum_s w[s] * Y[s*N + r][c] (stored in T when ysum != NULL, pitch = cols);
-// partials[p][c] = column sums of ysum over the rows of block p; returns nblk
+struct ColsumJob { const float *partials; int nblk, cols; float *out; int accumulate; };
+constexpr int kMaxColsumJobs = 8;
+struct ColsumJobs { int count; ColsumJob job[kMaxColsumJobs]; };
+// all second stages of one block's backward in a single launch
+hipError_t colsum_final_multi(const ColsumJobs &jobs, hipStream_t s);
+// partials[p][c] = column sums of ysum over the rows of block p; returns nblk.  (The second
+// stage stays a separate launch: a same-launch hand-over between workgroups needs a device-scope
+// fence, which on this multi-XCD part writes back the L2 and costs far more than a launch.)
 hipError_t sum_colsum(int dtype, const void *Y, int N, int cols, int ld, int ns, StreamWeights sw, void *ysum,
                       float *partials, int *nblk, hipStream_t s);
 int colsum_max_blocks();

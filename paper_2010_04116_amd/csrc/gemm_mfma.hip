@@ -49,7 +49,7 @@ __device__ inline void unpack8(const u32x4 v, float (&f)[8]) {
 __device__ inline u32x4 pack8(const float (&f)[8]) {
   u32x4 v;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) v[i] = (uint32_t)f32_to_bf16(f[2 * i]) | ((uint32_t)f32_to_bf16(f[2 * i + 1]) << 16);
+  for (int i = 0; i < 4; ++i) v[i] = pack_bf16x2(f[2 * i], f[2 * i + 1]);
   return v;
 }
 

@@ -174,7 +174,7 @@ struct il_ctx {
   std::vector<size_t> hoff;        // K
   std::vector<BlockSave> save;     // K*L
   float *G; char *Gb;              // stream slots [nslots][N,d]
-  char *DU, *DH, *DQKV, *YS[4]; float *dsum, *partials, *skws; size_t skws_floats;
+  char *DU, *DH, *DQKV, *YS[4]; float *dsum, *partials[6], *skws; size_t skws_floats; ColsumJobs jobs;
   char *xb, *Z; float *rowloss, *dxh;
   int Nc;
   std::vector<char> fwd_done, head_done, bwd_done;
@@ -235,7 +235,8 @@ size_t layout_workspace(il_ctx *c, void *base) {
   c->skws = (float *)cv.take(c->skws_floats * 4);
   size_t pcols = std::max((size_t)3 * d, m);
   size_t pbytes = std::max((size_t)ln_backward_max_blocks() * 2 * d, (size_t)colsum_max_blocks() * pcols) * 4;
-  c->partials = (float *)cv.take(pbytes);
+  for (int i = 0; i < 6; ++i) c->partials[i] = (float *)cv.take(pbytes);
+  c->jobs.count = 0;
   c->xb = (char *)cv.take(N * d * eb);
   c->Z = (char *)cv.take((size_t)c->Nc * c->V * eb);
   c->rowloss = (float *)cv.take(N * 4);
@@ -320,13 +321,13 @@ int linear_wgrad(il_ctx *c, const Run &cp, const void *x, const void *dy, int Ki
     Scope sc(c, KC_COLSUM, 0, (double)(in_place ? 1 : cp.nweighted + 1) * c->N * Nout * c->eb);
     if (in_place) {
       sw.w[0] = 1.f;
-      IL_TRY(sum_colsum(c->cfg.dtype, dys, c->N, Nout, Nout, 1, sw, nullptr, c->partials, &nblk, c->stream));
+      IL_TRY(sum_colsum(c->cfg.dtype, dys, c->N, Nout, Nout, 1, sw, nullptr, c->partials[slot], &nblk, c->stream));
     } else {
       memcpy(sw.w, cp.wt, sizeof(sw.w));
-      IL_TRY(sum_colsum(c->cfg.dtype, dy, c->N, Nout, Nout, cp.cnt, sw, c->YS[slot], c->partials, &nblk,
+      IL_TRY(sum_colsum(c->cfg.dtype, dy, c->N, Nout, Nout, cp.cnt, sw, c->YS[slot], c->partials[slot], &nblk,
                         c->stream));
     }
-    IL_TRY(colsum_final(c->partials, nblk, Nout, Gr(c, b_off), cp.acc, c->stream));
+    c->jobs.job[c->jobs.count++] = ColsumJob{c->partials[slot], nblk, Nout, Gr(c, b_off), cp.acc};
   }
   GemmArgs g = base_args();
   g.A = x; g.lda = Kin; g.a_kmajor = 1;
@@ -375,15 +376,15 @@ int attention_bwd(il_ctx *c, const BlockSave &s, const void *d_o, int cnt, void 
 }
 
 int ln_bwd(il_ctx *c, const Run &cp, const void *dy, const float *x, const float *stats, size_t g_off,
-           float *G, void *Gb) {
+           float *G, void *Gb, int slot) {
   StreamWeights sw;
   memcpy(sw.w, cp.wt, sizeof(sw.w));
   const int rows = cp.cnt * c->N;
   int nblk = 0;
   Scope sc(c, KC_LN_BWD, 0, (double)rows * c->d * (c->eb + 8 + c->eb) + (double)c->N * c->d * 4);
-  IL_TRY(ln_backward_residual(c->cfg.dtype, dy, x, stats, P(c, g_off), rows, c->N, c->d, G, Gb, sw, c->partials,
-                              &nblk, c->stream));
-  if (cp.nweighted) IL_TRY(colsum_final(c->partials, nblk, 2 * c->d, Gr(c, g_off), cp.acc, c->stream));
+  IL_TRY(ln_backward_residual(c->cfg.dtype, dy, x, stats, P(c, g_off), rows, c->N, c->d, G, Gb, sw,
+                              c->partials[slot], &nblk, c->stream));
+  if (cp.nweighted) c->jobs.job[c->jobs.count++] = ColsumJob{c->partials[slot], nblk, 2 * c->d, Gr(c, g_off), cp.acc};
   return IL_OK;
 }
 
@@ -414,19 +415,25 @@ int block_backward(il_ctx *c, const Run &cp, const BlockOff &b, const BlockSave 
   char *Gb = c->Gb + (size_t)cp.s0 * N * d * c->eb;
   int rc, nw = 0;
   GemmArgs wg[4];
+  c->jobs.count = 0;
   // MLP
   if ((rc = linear_dgrad(c, Gb, b.w_fc2, S, m, d, EPI_GELU_BWD, c->DU, s.u, N))) return rc;
   if ((rc = linear_wgrad(c, cp, s.gl, Gb, m, d, b.w_fc2, b.b_fc2, 0, true, wg, &nw))) return rc;
   if ((rc = linear_wgrad(c, cp, s.h2, c->DU, d, m, b.w_fc1, b.b_fc1, 1, false, wg, &nw))) return rc;
   if ((rc = linear_dgrad(c, c->DU, b.w_fc1, S, d, m, EPI_STORE, c->DH, nullptr, 0))) return rc;
-  if ((rc = ln_bwd(c, cp, c->DH, s.a, s.st2, b.ln2_g, G, Gb))) return rc;
+  if ((rc = ln_bwd(c, cp, c->DH, s.a, s.st2, b.ln2_g, G, Gb, 4))) return rc;
   // attention
   if ((rc = linear_wgrad(c, cp, s.o, Gb, d, d, b.w_o, b.b_o, 2, true, wg, &nw))) return rc;
   if ((rc = linear_dgrad(c, Gb, b.w_o, S, d, d, EPI_STORE, c->DH, nullptr, 0))) return rc;
   if ((rc = attention_bwd(c, s, c->DH, cp.cnt, c->DQKV))) return rc;
   if ((rc = linear_wgrad(c, cp, s.h1, c->DQKV, d, 3 * d, b.w_qkv, b.b_qkv, 3, false, wg, &nw))) return rc;
   if ((rc = linear_dgrad(c, c->DQKV, b.w_qkv, S, d, 3 * d, EPI_STORE, c->DH, nullptr, 0))) return rc;
-  if ((rc = ln_bwd(c, cp, c->DH, s.xs, s.st1, b.ln1_g, G, Gb))) return rc;
+  if ((rc = ln_bwd(c, cp, c->DH, s.xs, s.st1, b.ln1_g, G, Gb, 5))) return rc;
+  {  // second stage of the six column reductions (four bias gradients, two LayerNorm gain/bias pairs)
+    Scope sc(c, KC_COLSUM, 0, 0);
+    IL_TRY(colsum_final_multi(c->jobs, c->stream));
+    c->jobs.count = 0;
+  }
   return launch_wgrads(c, wg, nw);
 }
 

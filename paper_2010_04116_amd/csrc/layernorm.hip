@@ -76,8 +76,8 @@ template <> struct Vec<bf16_t, 4> {
   }
   static __device__ inline void store(bf16_t *p, const float (&o)[4]) {
     uint2 v;
-    v.x = (uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16);
-    v.y = (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16);
+    v.x = pack_bf16x2(o[0], o[1]);
+    v.y = pack_bf16x2(o[2], o[3]);
     *reinterpret_cast<uint2 *>(p) = v;
   }
 };

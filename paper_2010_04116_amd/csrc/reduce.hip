@@ -50,10 +50,10 @@ __global__ __launch_bounds__(256) void sum_colsum_kernel(const T *__restrict__ Y
       if (ysum) {
         if constexpr (V == 8) {
           uint4 q;
-          q.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
-          q.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
-          q.z = (uint32_t)f32_to_bf16(v[4]) | ((uint32_t)f32_to_bf16(v[5]) << 16);
-          q.w = (uint32_t)f32_to_bf16(v[6]) | ((uint32_t)f32_to_bf16(v[7]) << 16);
+          q.x = pack_bf16x2(v[0], v[1]);
+          q.y = pack_bf16x2(v[2], v[3]);
+          q.z = pack_bf16x2(v[4], v[5]);
+          q.w = pack_bf16x2(v[6], v[7]);
           *reinterpret_cast<uint4 *>(ysum + (size_t)r * cols + c) = q;
         } else {
           st<T>(ysum + (size_t)r * cols + c, v[0]);
@@ -149,7 +149,6 @@ inline int grid_for(size_t count) {
 }  // namespace
 
 int colsum_max_blocks() { return kColBlocksY; }
-
 hipError_t sum_colsum(int dtype, const void *Y, int N, int cols, int ldy, int ns, StreamWeights sw, void *ysum,
                       float *partials, int *nblk, hipStream_t s) {
   int nby = (N + 63) / 64;
@@ -165,6 +164,34 @@ hipError_t sum_colsum(int dtype, const void *Y, int N, int cols, int ldy, int ns
   else
     hipLaunchKernelGGL((sum_colsum_kernel<bf16_t, 1>), dim3((cols + 63) / 64, nby), dim3(256), 0, s,
                        (const bf16_t *)Y, N, cols, ldy, ns, sw, (bf16_t *)ysum, partials);
+  return hipGetLastError();
+}
+
+// Several second stages in one launch: grid.y selects the job.
+__global__ __launch_bounds__(256) void colsum_final_multi_kernel(ColsumJobs jobs) {
+  __shared__ float red[16][17];
+  const ColsumJob &jb = jobs.job[blockIdx.y];
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + tx;
+  if (blockIdx.x * 16 >= jb.cols) return;  // uniform across the block
+  float acc = 0.f;
+  if (c < jb.cols)
+    for (int p = ty; p < jb.nblk; p += 16) acc += jb.partials[(size_t)p * jb.cols + c];
+  red[ty][tx] = acc;
+  __syncthreads();
+  if (ty == 0 && c < jb.cols) {
+    float v = jb.accumulate ? jb.out[c] : 0.f;
+#pragma unroll
+    for (int y = 0; y < 16; ++y) v += red[y][tx];
+    jb.out[c] = v;
+  }
+}
+
+hipError_t colsum_final_multi(const ColsumJobs &jobs, hipStream_t s) {
+  if (jobs.count < 1) return hipSuccess;
+  int maxc = 0;
+  for (int i = 0; i < jobs.count; ++i) maxc = jobs.job[i].cols > maxc ? jobs.job[i].cols : maxc;
+  hipLaunchKernelGGL(colsum_final_multi_kernel, dim3((maxc + 15) / 16, jobs.count), dim3(256), 0, s, jobs);
   return hipGetLastError();
 }
 
