@@ -42,15 +42,21 @@ template <typename T> __device__ inline void st(T *p, float v);
 template <> __device__ inline void st<float>(float *p, float v) { *p = v; }
 template <> __device__ inline void st<bf16_t>(bf16_t *p, float v) { *p = f32_to_bf16(v); }
 
-// tanh-form GELU and its derivative, fp32.
+// tanh-form GELU and its derivative, fp32.  tanh(y) = 1 - 2/(exp(2y)+1) through the hardware
+// exp2 and reciprocal (relative error ~1e-6, far inside the fp32 tolerance; saturates correctly
+// for large |y|): the library tanhf costs several times more and sat in every MLP epilogue.
+__device__ inline float tanh_fast(float y) {
+  const float e = __builtin_amdgcn_exp2f(y * 2.8853900817779268f);  // exp(2y)
+  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f);
+}
 __device__ inline float gelu_f(float u) {
   const float c = 0.7978845608028654f;
-  float t = tanhf(c * (u + 0.044715f * u * u * u));
+  const float t = tanh_fast(c * (u + 0.044715f * u * u * u));
   return 0.5f * u * (1.0f + t);
 }
 __device__ inline float gelu_grad_f(float u) {
   const float c = 0.7978845608028654f;
-  float t = tanhf(c * (u + 0.044715f * u * u * u));
+  const float t = tanh_fast(c * (u + 0.044715f * u * u * u));
   return 0.5f * (1.0f + t) + 0.5f * u * (1.0f - t * t) * c * (1.0f + 0.134145f * u * u);
 }
 
