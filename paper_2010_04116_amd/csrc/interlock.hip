@@ -178,6 +178,11 @@ struct il_ctx {
   char *xb, *Z; float *rowloss, *dxh;
   int Nc;
   std::vector<char> fwd_done, head_done, bwd_done;
+  // heads run on a side stream, concurrently with the next component's forward
+  hipStream_t main_stream = nullptr, side = nullptr;
+  hipEvent_t ev_fork = nullptr;
+  std::vector<hipEvent_t> ev_head;   // K: head k finished (side stream)
+  std::vector<char> head_pending;    // main stream has not yet waited for ev_head[k]
   // profiling
   std::vector<ProfRec> recs; size_t nrec = 0;
   double flops[KC_COUNT] = {}, bytes[KC_COUNT] = {};
@@ -498,6 +503,7 @@ int il_init(il_config *cfg, il_ctx **out) {
   c->H = cfg->n_heads; c->dh = c->d / c->H; c->N = cfg->batch * cfg->seq;
   c->eb = cfg->dtype == IL_F32 ? 4 : 2;
   c->stream = (hipStream_t)cfg->stream;
+  c->main_stream = c->stream;
   rc = build_plan(c->K, cfg->n, cfg->route, c->plan);
   if (rc) { delete c; return rc; }
   int nc = cfg->head_chunk;
@@ -523,6 +529,7 @@ int il_init(il_config *cfg, il_ctx **out) {
     return IL_E_WORKSPACE;
   }
   c->fwd_done.assign(c->K + 1, 0); c->head_done.assign(c->K + 1, 0); c->bwd_done.assign(c->K + 2, 0);
+  c->head_pending.assign(c->K + 1, 0);
   *out = c;
   return IL_OK;
 }
@@ -556,6 +563,24 @@ int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets,
   if (!c->fwd_done[k]) return IL_E_STATE;
   const int N = c->N, d = c->d, V = c->V, dt = c->cfg.dtype;
   const size_t eb = c->eb;
+  // Head k only needs x_k; it runs on a side stream so that the next component's forward (and,
+  // later, other heads' consumers) overlap with it.  il_stage_backward_nwise(k) joins.
+  struct StreamSwap {
+    il_ctx *c; bool on;
+    ~StreamSwap() { if (on) c->stream = c->main_stream; }
+  } swap{c, false};
+  if (!c->cfg.profile) {
+    if (!c->side) {
+      IL_TRY(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+      IL_TRY(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
+      c->ev_head.assign(c->K + 1, nullptr);
+      for (int j = 1; j <= c->K; ++j) IL_TRY(hipEventCreateWithFlags(&c->ev_head[j], hipEventDisableTiming));
+    }
+    IL_TRY(hipEventRecord(c->ev_fork, c->main_stream));
+    IL_TRY(hipStreamWaitEvent(c->side, c->ev_fork, 0));
+    c->stream = c->side;
+    swap.on = true;
+  }
   {
     Scope sc(c, KC_MISC, 0, (double)N * d * (4 + eb));
     IL_TRY(convert_f32(dt, x_k, c->xb, (size_t)N * d, c->stream));
@@ -600,6 +625,10 @@ int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets,
     Scope sc(c, KC_MISC, 0, (double)N * 4);
     IL_TRY(sum_scalar(c->rowloss, N, 1.f / N, loss_out, c->stream));
   }
+  if (swap.on) {
+    IL_TRY(hipEventRecord(c->ev_head[k], c->side));
+    c->head_pending[k] = 1;
+  }
   c->head_done[k] = 1;
   return IL_OK;
 }
@@ -612,6 +641,12 @@ int il_stage_backward_nwise(il_ctx *c, int32_t k, float *dx0_out) {
   if (c->bwd_done[k] || (k < c->K && !c->bwd_done[k + 1])) return IL_E_STATE;
   const CompPlan &cp = c->plan.comp[k - 1];
   if (cp.inject_slot >= 0 && !c->head_done[k]) return IL_E_STATE;
+  // join the side stream: head k before its gradient is injected; every head before the step ends
+  for (int j = (k == 1 ? 1 : k); j <= (k == 1 ? c->K : k); ++j)
+    if (c->head_pending[j]) {
+      IL_TRY(hipStreamWaitEvent(c->stream, c->ev_head[j], 0));
+      c->head_pending[j] = 0;
+    }
   const size_t nd = (size_t)c->N * c->d;
   if (cp.inject_slot >= 0) {
     Scope sc(c, KC_MISC, 0, (double)nd * (8 + c->eb));
@@ -685,6 +720,9 @@ int il_test_gemm(int32_t dtype, const void *A, const void *B, int32_t M, int32_t
 int il_free(il_ctx *c) {
   if (!c) return IL_E_ARG;
   for (auto &r : c->recs) { hipEventDestroy(r.e0); hipEventDestroy(r.e1); }
+  for (hipEvent_t e : c->ev_head) if (e) hipEventDestroy(e);
+  if (c->ev_fork) hipEventDestroy(c->ev_fork);
+  if (c->side) { hipStreamSynchronize(c->side); hipStreamDestroy(c->side); }
   delete c;
   return IL_OK;
 }
