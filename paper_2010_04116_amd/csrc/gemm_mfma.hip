@@ -333,13 +333,8 @@ hipError_t pick_tile(GemmBatch &b, hipStream_t s) {
     default: break;
   }
   // Measured on MI355X: with enough 256x256 tiles to cover most of the 256 CUs the large tile
-  // wins (8 wavefronts; 4 when both operands take the transposing read); below that the
-  // 128x128 tile, two workgroups per CU, keeps more CUs busy.
-  if (AKM && BKM) {
-    if (t256 >= 200) return launch_dma<256, 256, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
-  } else if (t256 >= 160) {
-    return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI>(b, s);
-  }
+  // (8 wavefronts) wins; below that the 128x128 tile, two workgroups per CU, keeps more CUs busy.
+  if (t256 >= 160) return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI>(b, s);
   return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
 }
 
