@@ -5,7 +5,10 @@ A step is the whole hot path: K x (il_stage_forward + il_head_xent) and the n-wi
 truncated backward il_stage_backward_nwise for k = K..1, all parameter gradients final,
 on seeded synthetic tokens already resident in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps 20] [--warmup 5] [--workload small] [--n N]
+    python bench.py [--gpus 1] [--steps 20] [--warmup 5] [--workload small] [--n N] [--also medium]
+
+`value` is the workload named by --workload (default: the Small configuration); the workloads
+named by --also are measured the same way and reported under "other_workloads".
 """
 import argparse
 import json
@@ -72,6 +75,7 @@ def kernel_table(w, flat, steps):
     prof = binding.il_profile_read(st.ctx)
     st.close()
     for v in prof.values():
+        v["steps"] = steps
         v["ms_per_step"] = v["ms"] / steps
         v["flops_per_step"] = v["flops"] / steps
         v["bytes_per_step"] = v["bytes"] / steps
@@ -102,27 +106,10 @@ def cpu_baseline(w, params, x0, tgt):
 INPUTS = None
 
 
-def main():
+def measure(w, steps, warmup):
+    """Time `steps` whole steps of workload w, then the per-class table in a profiling context."""
     global INPUTS
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="small")
-    ap.add_argument("--n", type=int, default=0, help="override the workload's window")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    a = ap.parse_args()
-    if a.gpus != 1:
-        sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); depthwise sharding "
-                 "across GPUs is described in DESIGN.md and not built")
-    if int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        sys.exit("bench.py: launched with WORLD_SIZE > 1; this build runs on exactly one GPU")
-
-    import torch
     from paper_2010_04116_amd import binding, synth
-    w = synth.WORKLOADS[a.workload]
-    if a.n:
-        w = w.with_(n=a.n)
     params = synth.make_params(w)                      # N(0,0.02) weights, biases 0, LN 1/0
     inp, tgt = synth.make_tokens(w)
     x0 = synth.make_x0(w, inp)
@@ -131,36 +118,35 @@ def main():
 
     st = binding.Step(w, flat)
     st.set_inputs(x0, tgt)
-    ms, wall_ms = time_steps(st, a.steps, a.warmup)
+    ms, wall_ms = time_steps(st, steps, warmup)
     losses = st.results()["losses"]
     st.close()
     # uniform random tokens: every loss sits at ln V plus half the logit variance, which grows with depth
     assert np.all(np.isfinite(losses)) and np.all(losses > np.log(w.V) - 0.5) and np.all(losses < 4 * np.log(w.V)), losses
 
-    prof = kernel_table(w, flat, max(2, min(a.steps, 5)))
+    prof = kernel_table(w, flat, max(2, min(steps, 5)))
     flops = minimal_flops(w)
-    tokens_per_s = w.N / (ms * 1e-3)
     gemm = [k for k in prof if k.startswith("gemm")]
-    g_ms = sum(prof[k]["ms_per_step"] for k in gemm)
     g_fl = sum(prof[k]["flops_per_step"] for k in gemm)
     g_n = sum(prof[k]["launches_per_step"] for k in gemm)
-    peak = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_F32_TFLOPS
+    if w.dtype == "bf16":
+        # events attached to each MFMA GEMM dispatch: the kernel's own execution time
+        g_ms = sum(prof[k]["kernel_ms"] for k in gemm) / prof[gemm[0]]["steps"]
+        peak, how = PEAK_BF16_TFLOPS, "HIP events attached to each GEMM kernel dispatch"
+    else:
+        g_ms = sum(prof[k]["ms_per_step"] for k in gemm)
+        peak, how = PEAK_F32_TFLOPS, "HIP events recorded around each GEMM launch"
     achieved = g_fl / (g_ms * 1e-3) / 1e12 if g_ms > 0 else 0.0
-    out = {
-        "metric": "tokens/sec per n-wise train step at 1 GPU",
-        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
-        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": f"{w.name}_{w.dtype}_n{w.n}", "K": w.K, "blocks_per_component": w.L,
-                   "d_model": w.d, "n_heads": w.H, "d_mlp": w.m, "vocab": w.V, "batch": w.B, "seq": w.T,
-                   "n": w.n, "route": "window_sum", "param_seed": synth.PARAM_SEED,
-                   "token_seed": synth.TOKEN_SEED},
+    res = {
+        "ms_per_step": ms, "wall_ms_per_step": wall_ms, "tokens_per_s": w.N / (ms * 1e-3),
         "mfma_utilisation_pct_of_bf16_peak": 100.0 * flops / (ms * 1e-3) / (PEAK_BF16_TFLOPS * 1e12),
         "algorithmic_tflop_per_step": flops / 1e12,
-        "wall_ms_per_step": wall_ms,
-        "roofline": {"bound": "mfma", "kernel": "gemm (forward, dgrad, wgrad, head) launches of one step",
+        "roofline": {"bound": "mfma" if w.dtype == "bf16" else "alu",
+                     "kernel": "gemm_dma_kernel: every GEMM launch of one step (forward, dgrad, wgrad, head)"
+                     if w.dtype == "bf16" else "gemm_simt_kernel: every GEMM launch of one step",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-                     "traffic": None, "launches_per_step": g_n, "avg_launch_ms": g_ms / max(g_n, 1)},
+                     "traffic": None, "launches_per_step": g_n, "avg_launch_ms": g_ms / max(g_n, 1),
+                     "algorithmic_gflop_per_launch": g_fl / max(g_n, 1) / 1e9, "timing": how},
         "kernels": {k: {"ms_per_step": round(v["ms_per_step"], 4), "launches": v["launches_per_step"],
                         "tflops": (v["flops_per_step"] / (v["ms_per_step"] * 1e-3) / 1e12)
                         if v["ms_per_step"] > 0 and v["flops_per_step"] else None,
@@ -169,8 +155,57 @@ def main():
                     for k, v in prof.items()},
         "losses": [float(x) for x in losses],
     }
+    return res, params, x0, tgt
+
+
+def config_of(w):
+    from paper_2010_04116_amd import synth
+    return {"workload": f"{w.name}_{w.dtype}_n{w.n}", "K": w.K, "blocks_per_component": w.L,
+            "d_model": w.d, "n_heads": w.H, "d_mlp": w.m, "vocab": w.V, "batch": w.B, "seq": w.T,
+            "n": w.n, "route": "window_sum", "param_seed": synth.PARAM_SEED, "token_seed": synth.TOKEN_SEED}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="small")
+    ap.add_argument("--n", type=int, default=0, help="override the workload's window")
+    ap.add_argument("--also", default="medium",
+                    help="comma-separated further workloads reported under other_workloads ('' = none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); depthwise sharding "
+                 "across GPUs is described in DESIGN.md and not built")
+    if int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: launched with WORLD_SIZE > 1; this build runs on exactly one GPU")
+
+    from paper_2010_04116_amd import synth
+    w = synth.WORKLOADS[a.workload]
+    if a.n:
+        w = w.with_(n=a.n)
+    res, params, x0, tgt = measure(w, a.steps, a.warmup)
+    out = {
+        "metric": "tokens/sec per n-wise train step at 1 GPU",
+        "value": res.pop("tokens_per_s"), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": res.pop("ms_per_step"), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic", "config": config_of(w),
+    }
+    out.update(res)
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, params, x0.astype(np.float64), tgt)
+    del params, x0, tgt
+    others = {}
+    for name in [x for x in a.also.split(",") if x and x != "none" and x != a.workload]:
+        wo = synth.WORKLOADS[name]
+        ro = measure(wo, min(a.steps, 10), min(a.warmup, 3))[0]
+        ro.pop("kernels"); ro.pop("losses")
+        ro["config"] = config_of(wo)
+        others[wo.name] = ro
+    if others:
+        out["other_workloads"] = others
     print(json.dumps(out))
 
 

@@ -11,8 +11,14 @@
  *
  * All pointers named "device" are HIP device pointers owned by the caller.  The
  * library allocates no device memory: parameters, gradients, the workspace and the
- * stream come from the caller.  All work is enqueued asynchronously on
- * il_config.stream; the caller synchronises that stream before reading results.
+ * stream come from the caller.  All work is enqueued asynchronously, ordered with
+ * il_config.stream: the caller synchronises that stream before reading results.  (The
+ * context owns one further non-blocking stream and a few events, on which il_head_xent
+ * runs concurrently with the next component's forward; il_stage_backward_nwise and
+ * il_head_xent(K), the step's last head, join it back into il_config.stream, so the caller
+ * never sees it.  A loss or a head gradient is therefore final on il_config.stream once the
+ * call that joins it has been enqueued; until then the x_k and targets buffers handed to
+ * il_head_xent must not be overwritten.)
  * Every function returns an il_status; nothing is printed and nothing aborts.
  *
  * Components and heads are numbered 1..K as in the paper.
@@ -99,9 +105,10 @@ typedef struct il_config {
  * Validate cfg and create a context (host memory only).
  * Size query: call with cfg->workspace == NULL; the three *_bytes fields are filled
  * with the required sizes, *out is left NULL and IL_E_WORKSPACE is returned.
- * Limits: d_model % n_heads == 0; head width d/n_heads in {16, 32, 64, 128};
- * d_model <= 2048*... see IL_E_SHAPE: d_model, d_mlp, vocab multiples of 8 and
- * batch*seq a multiple of 64 in bf16 mode; at most 16 live gradient streams per component.
+ * Limits (IL_E_SHAPE otherwise): d_model a multiple of n_heads with head width
+ * d_model / n_heads in {16, 32, 64, 128}; d_model <= 2048; batch*seq <= 2^24; vocab <= 2^24;
+ * in bf16 mode d_model, d_mlp and vocab multiples of 8, batch*seq and head_chunk multiples of
+ * 64.  At most 16 merged gradient streams may be live at one component.
  * The workspace must be 256-byte aligned.
  */
 int il_init(il_config *cfg, il_ctx **out);
@@ -155,12 +162,17 @@ int il_routing_plan(int32_t K, int32_t n, int32_t route, int32_t *live, int32_t 
 
 /*
  * Profiling (cfg.profile != 0): synchronises the stream and returns, per kernel class,
- * launches and total milliseconds since the last call, measured with HIP events on the
- * library's stream.  `names` receives pointers to static strings.  Returns the number of
- * classes written (<= cap), or a negative il_status.
+ * launches and total milliseconds since the last call, measured with HIP events recorded
+ * on the library's stream before and after each launch group (`ms`; this includes the few
+ * microseconds an event costs between launches), the algorithmic flops and bytes of those
+ * launches, and for the bf16 GEMM classes `kernel_ms`: the execution time of the MFMA GEMM
+ * kernels alone, from events attached to each dispatch (0 for the other classes).  In
+ * profiling mode the heads run on the caller's stream instead of the internal side stream.
+ * `names` receives pointers to static strings; any output array may be NULL.  Returns the
+ * number of classes written (<= cap), or a negative il_status.
  */
 int il_profile_read(il_ctx *ctx, int32_t cap, const char **names, int64_t *launches, double *ms,
-                    double *flops, double *bytes);
+                    double *flops, double *bytes, double *kernel_ms);
 
 /*
  * Kernel-level test hook: one GEMM launch of the library's own kernels, outside any step, so
@@ -172,7 +184,7 @@ int il_profile_read(il_ctx *ctx, int32_t cap, const char **names, int64_t *launc
  *      3 +bias +res (fp32 out) | 4 * GELU'(aux[row % aux_wrap]) (T) | 5 store fp32 |
  *      6 C = scale*acc (+ C if beta) (fp32);
  * tile: 0 = library's choice, else 1 = 256x256 / 4 wavefronts, 2 = 256x256 / 8 wavefronts,
- *       3 = 128x128 / 4 wavefronts (bf16 only).
+ *       3 = 128x128 / 4 wavefronts, 4 = 64x64 / 4 wavefronts (bf16 only).
  * All pointers are device pointers; unused ones may be NULL.  Returns an il_status.
  */
 int il_test_gemm(int32_t dtype, const void *A, const void *B, int32_t M, int32_t N, int32_t K, int32_t lda,

@@ -58,7 +58,8 @@ def load():
     lib.il_free.argtypes = [vp]
     lib.il_routing_plan.argtypes = [i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
     lib.il_profile_read.argtypes = [vp, i32, C.POINTER(C.c_char_p), C.POINTER(C.c_int64),
-                                    C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double)]
+                                    C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                    C.POINTER(C.c_double)]
     lib.il_test_gemm.argtypes = [i32, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, i32, vp, vp, vp,
                                  i32, C.c_float, i32, i32, vp]
     lib.il_status_string.argtypes = [C.c_int]
@@ -158,10 +159,12 @@ def il_profile_read(ctx) -> Dict[str, dict]:
     ms = (C.c_double * cap)()
     fl = (C.c_double * cap)()
     by = (C.c_double * cap)()
-    cnt = load().il_profile_read(ctx, cap, names, n, ms, fl, by)
+    kms = (C.c_double * cap)()
+    cnt = load().il_profile_read(ctx, cap, names, n, ms, fl, by, kms)
     if cnt < 0:
         raise InterlockError(cnt, "il_profile_read")
-    return {names[i].decode(): dict(launches=n[i], ms=ms[i], flops=fl[i], bytes=by[i]) for i in range(cnt)}
+    return {names[i].decode(): dict(launches=n[i], ms=ms[i], flops=fl[i], bytes=by[i], kernel_ms=kms[i])
+            for i in range(cnt)}
 
 
 # --------------------------------------------------------------------------------------

@@ -16,6 +16,7 @@
 // fixed reduction order (no atomics): one owns a key/value tile and accumulates dK, dV over
 // the query tiles at or below the diagonal, the other owns a query tile and accumulates dQ.
 #include "common.h"
+#include "lds_dma.h"
 
 namespace il {
 namespace {
@@ -23,12 +24,10 @@ namespace {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4v;
-typedef __attribute__((address_space(3))) void lds_void;
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kNegBig = -1.0e30f;
-constexpr uint32_t kOob = 0x80000000u;  // byte offset past every buffer: the load returns 0
 
 __device__ inline uint4 ldg16(const bf16_t *p) { return *reinterpret_cast<const uint4 *>(p); }
 __device__ inline uint32_t pack2(float a, float b) {
@@ -41,10 +40,6 @@ union Frag {
   uint32_t u[4];
   short4v s[2];
 };
-__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *base, size_t bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
-}
-constexpr int vmcnt0_imm() { return (7 << 4) | (15 << 8); }
 
 // A [ROWS tokens] x [DH] tile of a token-major matrix, staged as is ([token][dh]) by direct
 // loads (256 threads, 16 bytes each per round).  The 16-byte chunk c of row r sits at chunk
@@ -70,17 +65,13 @@ struct TokTile {
     }
   }
   // rows [row0, row0 + ROWS) of the matrix; rows >= row_end read as zero
-  __device__ inline void issue(__amdgpu_buffer_rsrc_t rs, char *lds, int wave, int row0, int row_end) const {
+  __device__ inline void issue(BufRsrc rs, char *lds, int wave, int row0, int row_end) const {
     const uint32_t adv = (uint32_t)row0 * rstride;
+    const uint32_t base = lds_address(lds) + wave * 1024;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const bool ok = row0 + radd[i] < row_end;
-#if defined(__HIP_DEVICE_COMPILE__)  // the host pass cannot type-check this builtin
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(lds + (i * 256 + wave * 64) * 16), 16,
-                                               ok ? voff[i] + adv : kOob, 0, 0, 0);
-#else
-      (void)rs; (void)lds; (void)wave; (void)ok; (void)adv;
-#endif
+      dma16(rs, base + i * 4096, ok ? voff[i] + adv : kOob);
     }
   }
   // MFMA operand with the tile's rows as matrix rows and dh as k: rows rbase + (lane & 31),
@@ -139,7 +130,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16_t *__restrict__ 
   float m = kNegBig, l = 0.f;
   const float sc = rsqrtf((float)DH) * kLog2e;
 
-  const __amdgpu_buffer_rsrc_t rs = make_rsrc(qbase, (size_t)T * ld3 * 2 - (size_t)h * DH * 2);
+  const BufRsrc rs = make_rsrc(qbase, (size_t)T * ld3 * 2 - (size_t)h * DH * 2);
   Tile lk, lv;
   lk.init(d, (int)ld3, t);
   lv.init(2 * d, (int)ld3, t);
@@ -149,7 +140,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16_t *__restrict__ 
   for (int kt = 0; kt < nkv; ++kt) {
     const char *sk = smem + (kt & 1) * STAGE, *sv = sk + KT;
     const int kv0 = kt * BKV;
-    __builtin_amdgcn_s_waitcnt(vmcnt0_imm());
+    wait_vmcnt<0>();
     __syncthreads();  // tile kt is complete; every wavefront is done with tile kt-1
     if (kt + 1 < nkv) {
       char *nk = smem + ((kt + 1) & 1) * STAGE;
@@ -292,7 +283,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t *__restrict
 #pragma unroll
     for (int r = 0; r < 16; ++r) dq[i][r] = 0.f;
 
-  const __amdgpu_buffer_rsrc_t rs = make_rsrc(qbase, (size_t)T * ld3 * 2 - (size_t)h * DH * 2);
+  const BufRsrc rs = make_rsrc(qbase, (size_t)T * ld3 * 2 - (size_t)h * DH * 2);
   Tile lk, lv;
   lk.init(d, (int)ld3, t);
   lv.init(2 * d, (int)ld3, t);
@@ -302,7 +293,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t *__restrict
   for (int kt = 0; kt < nkv; ++kt) {
     const char *sk = smem + (kt & 1) * STAGE, *sv = sk + KT;
     const int kv0 = kt * BKV;
-    __builtin_amdgcn_s_waitcnt(vmcnt0_imm());
+    wait_vmcnt<0>();
     __syncthreads();
     if (kt + 1 < nkv) {
       char *nk = smem + ((kt + 1) & 1) * STAGE;
@@ -408,23 +399,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t *__restric
   const float sc = rsqrtf((float)DH);
   const float sc2 = sc * kLog2e;
 
-  const __amdgpu_buffer_rsrc_t rq = make_rsrc(qbase, (size_t)T * ld3 * 2 - (size_t)h * DH * 2);
-  const __amdgpu_buffer_rsrc_t rg = make_rsrc(gbase, (size_t)T * d * 2 - (size_t)h * DH * 2);
+  const BufRsrc rq = make_rsrc(qbase, (size_t)T * ld3 * 2 - (size_t)h * DH * 2);
+  const BufRsrc rg = make_rsrc(gbase, (size_t)T * d * 2 - (size_t)h * DH * 2);
   Tile lq, lg;
   lq.init(0, (int)ld3, t);
   lg.init(0, d, t);
-  const __amdgpu_buffer_rsrc_t rl = make_rsrc(lrow, (size_t)T * 4), rd = make_rsrc(drow, (size_t)T * 4);
+  const BufRsrc rl = make_rsrc(lrow, (size_t)T * 4), rd = make_rsrc(drow, (size_t)T * 4);
   auto issue = [&](int qt, char *base) {  // direct loads of the Q and dO tiles and of 64 lse / dsum values
     const int r0 = qt * BQ;
     lq.issue(rq, base, wave, r0, T);
     lg.issue(rg, base + QT, wave, r0, T);
-#if defined(__HIP_DEVICE_COMPILE__)
-    if (wave == 0)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rl, (lds_void *)(base + 2 * QT), 4, (uint32_t)(r0 + lane) * 4u, 0, 0, 0);
-    if (wave == 1)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rd, (lds_void *)(base + 2 * QT + BQ * 4), 4,
-                                               (uint32_t)(r0 + lane) * 4u, 0, 0, 0);
-#endif
+    if (wave == 0) dma4(rl, lds_address(base + 2 * QT), (uint32_t)(r0 + lane) * 4u);
+    if (wave == 1) dma4(rd, lds_address(base + 2 * QT + BQ * 4), (uint32_t)(r0 + lane) * 4u);
   };
   if (qt0 < nqt) issue(qt0, smem);
 
@@ -433,7 +419,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t *__restric
     const char *sq = smem + (it & 1) * STAGE, *sg = sq + QT;
     const float *sl = reinterpret_cast<const float *>(sq + 2 * QT), *sd = sl + BQ;
     const int qb0 = qt * BQ;
-    __builtin_amdgcn_s_waitcnt(vmcnt0_imm());
+    wait_vmcnt<0>();
     __syncthreads();
     if (qt + 1 < nqt) issue(qt + 1, smem + ((it + 1) & 1) * STAGE);
 #pragma unroll

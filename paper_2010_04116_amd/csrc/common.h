@@ -98,9 +98,16 @@ struct GemmArgs {
   float scale;        // EPI_WGRAD
   uint32_t a_bytes, b_bytes;  // operand extents in bytes (filled by the bf16 front end)
   int k_begin, k_end; // reduction range [k_begin, k_end); both 0 = all of K (used by split-K)
-  int tile;           // bf16: 0 = choose by shape, 1 = 256x256/4 waves, 2 = 256x256/8 waves, 3 = 128x128
+  int tile;           // bf16: 0 = choose by shape, 1 = 256x256/4 waves, 2 = 256x256/8 waves, 3 = 128x128, 4 = 64x64
   int beta;           // EPI_WGRAD: accumulate into C
 };
+
+// Events attached to ONE kernel dispatch (hipExtLaunchKernelGGL): elapsed(start, stop) is that
+// kernel's own execution time, the figure a kernel trace reports, without the gaps that events
+// recorded between launches add.  gemm_time_next() arms the calling thread's next bf16 GEMM
+// kernel launch; the launch disarms it.  Returns the timer that was still armed (nullptr if none).
+struct KernelTimer { hipEvent_t start, stop; };
+const KernelTimer *gemm_time_next(const KernelTimer *t);
 
 hipError_t gemm_f32(const GemmArgs &g, hipStream_t s);    // T = float, SIMT
 hipError_t gemm_bf16(const GemmArgs &g, hipStream_t s);   // T = bf16, MFMA

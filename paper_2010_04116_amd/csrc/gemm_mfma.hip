@@ -21,7 +21,10 @@
 #include <algorithm>
 #include <cstring>
 
+#include <hip/hip_ext.h>
+
 #include "common.h"
+#include "lds_dma.h"
 
 namespace il {
 namespace {
@@ -29,15 +32,6 @@ namespace {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
-
-constexpr uint32_t kOob = 0x80000000u;  // byte offset beyond every operand: the buffer load returns 0
-
-// Raw buffer descriptor over [base, base+bytes): loads past the end return zero, so tile
-// edges need no branches (the range check covers the VGPR offset; the scalar offset is
-// kept at zero because it is not part of the check).
-__device__ inline __amdgpu_buffer_rsrc_t make_rsrc(const void *base, uint32_t bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)bytes, 0x00020000);
-}
 
 __device__ inline void unpack8(const u32x4 v, float (&f)[8]) {
 #pragma unroll
@@ -147,7 +141,6 @@ __device__ inline void epilogue(const GemmArgs &g, floatx16 (&acc)[MI][NI], char
 // consecutive rows-elements of k-row kb + i/4, column group 4(i%4); the instruction hands
 // lane j the four k values kb..kb+3 of row j - exactly the MFMA operand order.
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4v;
-typedef __attribute__((address_space(3))) void lds_void;
 
 template <int ROWS, int BKT, bool KMAJOR, int NT>
 struct DmaTile {
@@ -181,17 +174,13 @@ struct DmaTile {
     }
   }
   // lds: stage base of this operand (wave-uniform); wave: wave id (uniform)
-  __device__ inline void issue(__amdgpu_buffer_rsrc_t rs, char *lds, int wave, int k0, int kend) const {
+  __device__ inline void issue(BufRsrc rs, char *lds, int wave, int k0, int kend) const {
     const uint32_t adv = (uint32_t)k0 * kstride;
+    const uint32_t base = lds_address(lds) + wave * 1024;
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const bool ok = k0 + kadd[i] < kend;
-#if defined(__HIP_DEVICE_COMPILE__)  // the host pass cannot type-check this builtin (it only needs the kernel's stub)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void *)(lds + (i * NT + wave * 64) * 16), 16,
-                                               ok ? voff[i] + adv : kOob, 0, 0, 0);
-#else
-      (void)rs; (void)lds; (void)wave; (void)ok; (void)adv;
-#endif
+      dma16(rs, base + i * (NT * 16), ok ? voff[i] + adv : kOob);
     }
   }
   // 32 x 16 MFMA fragment of rows [rbase, rbase+32), k slice ks of the staged K step
@@ -213,8 +202,6 @@ struct DmaTile {
     }
   }
 };
-
-constexpr int vmcnt_imm(int n) { return (n & 15) | ((n >> 4) << 14) | (7 << 4) | (15 << 8); }
 
 struct GemmBatch {
   int count;
@@ -252,7 +239,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmBatch batc
   const int tm = first_m + (pid % per_group) % gsize, tn = (pid % per_group) / gsize;
   const int m0 = tm * BM, n0 = tn * BN;
 
-  const __amdgpu_buffer_rsrc_t ra = make_rsrc(g.A, g.a_bytes), rb = make_rsrc(g.B, g.b_bytes);
+  const BufRsrc ra = make_rsrc(g.A, g.a_bytes), rb = make_rsrc(g.B, g.b_bytes);
   typedef DmaTile<BM, BKT, AKM, NT> TA;
   typedef DmaTile<BN, BKT, BKM, NT> TB;
   TA la;
@@ -285,9 +272,9 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmBatch batc
 
   for (int kt = 0; kt < nk; ++kt) {
     if (nk - 1 - kt >= NSTAGE - 2)
-      __builtin_amdgcn_s_waitcnt(vmcnt_imm((NSTAGE - 2) * LPS));
+      wait_vmcnt<(NSTAGE - 2) * LPS>();
     else
-      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+      wait_vmcnt<0>();
     __syncthreads();
     if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
     const char *sa = smem + (kt % NSTAGE) * STAGE;
@@ -310,6 +297,8 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmBatch batc
   epilogue<BM, BN, WGM, WGN, EPI>(g, acc, smem, m0, n0, wave, lane);
 }
 
+thread_local const KernelTimer *tl_timer = nullptr;  // armed by gemm_time_next()
+
 template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGE, bool AKM, bool BKM, int EPI>
 hipError_t launch_dma(GemmBatch &b, hipStream_t s) {
   int tiles = 0;
@@ -317,25 +306,38 @@ hipError_t launch_dma(GemmBatch &b, hipStream_t s) {
     tiles += ((b.p[i].M + BM - 1) / BM) * ((b.p[i].N + BN - 1) / BN);
     b.tile_end[i] = tiles;
   }
-  hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, BKT, NSTAGE, AKM, BKM, EPI>), dim3(tiles),
-                     dim3(64 * WGM * WGN), 0, s, b);
+  if (const KernelTimer *t = tl_timer) {
+    tl_timer = nullptr;
+    hipExtLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, BKT, NSTAGE, AKM, BKM, EPI>), dim3(tiles),
+                          dim3(64 * WGM * WGN), 0, s, t->start, t->stop, 0, b);
+  } else {
+    hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, BKT, NSTAGE, AKM, BKM, EPI>), dim3(tiles),
+                       dim3(64 * WGM * WGN), 0, s, b);
+  }
   return hipGetLastError();
 }
 
 template <bool AKM, bool BKM, int EPI>
 hipError_t pick_tile(GemmBatch &b, hipStream_t s) {
-  long t256 = 0;
-  for (int i = 0; i < b.count; ++i) t256 += (long)((b.p[i].M + 255) / 256) * ((b.p[i].N + 255) / 256);
+  long t256 = 0, t128 = 0;
+  for (int i = 0; i < b.count; ++i) {
+    t256 += (long)((b.p[i].M + 255) / 256) * ((b.p[i].N + 255) / 256);
+    t128 += (long)((b.p[i].M + 127) / 128) * ((b.p[i].N + 127) / 128);
+  }
   switch (b.p[0].tile) {
     case 1: return launch_dma<256, 256, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
     case 2: return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI>(b, s);
     case 3: return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
+    case 4: return launch_dma<64, 64, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
     default: break;
   }
   // Measured on MI355X: with enough 256x256 tiles to cover most of the 256 CUs the large tile
-  // (8 wavefronts) wins; below that the 128x128 tile, two workgroups per CU, keeps more CUs busy.
+  // (8 wavefronts) wins; below that the 128x128 tile, two workgroups per CU, keeps more CUs busy;
+  // and when even those leave CUs idle, 64x64 tiles (four workgroups per CU) shorten each
+  // workgroup's K loop, which is what bounds such a launch.
   if (t256 >= 160) return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI>(b, s);
-  return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
+  if (t128 >= 256) return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
+  return launch_dma<64, 64, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
 }
 
 // argument checks and buffer extents of one problem
@@ -382,6 +384,12 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
 }
 
 }  // namespace
+
+const KernelTimer *gemm_time_next(const KernelTimer *t) {
+  const KernelTimer *old = tl_timer;
+  tl_timer = t;
+  return old;
+}
 
 // The step uses exactly these (layout, epilogue) combinations; anything else is a
 // programming error in the caller and is reported instead of silently taking another path.

@@ -161,7 +161,7 @@ struct BlockSave {  // workspace pointers of one block's saved activations
   float *xs, *st1, *lse, *a, *st2;
   char *h1, *qkv, *o, *h2, *u, *gl;
 };
-struct ProfRec { int cls; hipEvent_t e0, e1; };
+struct ProfRec { int cls; bool kernel; hipEvent_t e0, e1; KernelTimer kt; };
 
 }  // namespace
 
@@ -257,14 +257,23 @@ struct Scope {  // brackets a group of launches with events when profiling is on
     c->flops[cls] += flops; c->bytes[cls] += bytes;
     if (c->nrec == c->recs.size()) {
       ProfRec n{};
-      if (hipEventCreate(&n.e0) != hipSuccess || hipEventCreate(&n.e1) != hipSuccess) return;
+      if (hipEventCreate(&n.e0) != hipSuccess || hipEventCreate(&n.e1) != hipSuccess ||
+          hipEventCreate(&n.kt.start) != hipSuccess || hipEventCreate(&n.kt.stop) != hipSuccess)
+        return;
       c->recs.push_back(n);
     }
     r = &c->recs[c->nrec++];
     r->cls = cls;
+    // bf16 GEMM scopes also time their MFMA kernel launch by itself (events on the dispatch)
+    r->kernel = c->cfg.dtype == IL_BF16 && cls <= KC_GEMM_HEAD;
+    if (r->kernel) gemm_time_next(&r->kt);
     hipEventRecord(r->e0, c->stream);
   }
-  ~Scope() { if (r) hipEventRecord(r->e1, c->stream); }
+  ~Scope() {
+    if (!r) return;
+    if (gemm_time_next(nullptr)) r->kernel = false;  // no MFMA GEMM was launched in this scope
+    hipEventRecord(r->e1, c->stream);
+  }
 };
 
 #define IL_TRY(expr) do { hipError_t e_ = (expr); if (e_ != hipSuccess) return IL_E_HIP; } while (0)
@@ -541,6 +550,13 @@ int il_stage_forward(il_ctx *c, int32_t k, const float *x_in, float *x_out) {
     std::fill(c->fwd_done.begin(), c->fwd_done.end(), 0);
     std::fill(c->head_done.begin(), c->head_done.end(), 0);
     std::fill(c->bwd_done.begin(), c->bwd_done.end(), 0);
+    // an abandoned step may have left heads running on the side stream: they share the scratch
+    // that this step's heads will use and read buffers the caller is about to overwrite
+    for (int j = 1; j <= c->K; ++j)
+      if (c->head_pending[j]) {
+        if (hipStreamWaitEvent(c->stream, c->ev_head[j], 0) != hipSuccess) return IL_E_HIP;
+        c->head_pending[j] = 0;
+      }
   } else if (!c->fwd_done[k - 1]) {
     return IL_E_STATE;
   }
@@ -628,6 +644,13 @@ int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets,
   if (swap.on) {
     IL_TRY(hipEventRecord(c->ev_head[k], c->side));
     c->head_pending[k] = 1;
+    // The last head joins the side stream back (it is in order, so this covers every earlier head):
+    // component K's backward needs this head at once anyway, and a caller that stops after the
+    // heads finds every loss final on its own stream.
+    if (k == c->K) {
+      IL_TRY(hipStreamWaitEvent(c->main_stream, c->ev_head[k], 0));
+      std::fill(c->head_pending.begin(), c->head_pending.end(), 0);
+    }
   }
   c->head_done[k] = 1;
   return IL_OK;
@@ -674,22 +697,27 @@ int il_stage_backward_nwise(il_ctx *c, int32_t k, float *dx0_out) {
 }
 
 int il_profile_read(il_ctx *c, int32_t cap, const char **names, int64_t *launches, double *ms, double *flops,
-                    double *bytes) {
+                    double *bytes, double *kernel_ms) {
   if (!c || cap < 0) return IL_E_ARG;
   if (hipStreamSynchronize(c->stream) != hipSuccess) return IL_E_HIP;
-  double t[KC_COUNT] = {};
+  double t[KC_COUNT] = {}, tk[KC_COUNT] = {};
   int64_t n[KC_COUNT] = {};
   for (size_t i = 0; i < c->nrec; ++i) {
     float e = 0.f;
     if (hipEventElapsedTime(&e, c->recs[i].e0, c->recs[i].e1) != hipSuccess) return IL_E_HIP;
     t[c->recs[i].cls] += e;
     n[c->recs[i].cls] += 1;
+    if (c->recs[i].kernel) {
+      if (hipEventElapsedTime(&e, c->recs[i].kt.start, c->recs[i].kt.stop) != hipSuccess) return IL_E_HIP;
+      tk[c->recs[i].cls] += e;
+    }
   }
   const int cnt = std::min<int>(cap, KC_COUNT);
   for (int i = 0; i < cnt; ++i) {
     if (names) names[i] = kClassNames[i];
     if (launches) launches[i] = n[i];
     if (ms) ms[i] = t[i];
+    if (kernel_ms) kernel_ms[i] = tk[i];
     if (flops) flops[i] = c->flops[i];
     if (bytes) bytes[i] = c->bytes[i];
   }
@@ -705,7 +733,7 @@ int il_test_gemm(int32_t dtype, const void *A, const void *B, int32_t M, int32_t
                  int32_t beta, int32_t tile, void *stream) {
   if (!A || !B || !C || M < 1 || N < 1 || K < 1) return IL_E_ARG;
   if (dtype != IL_F32 && dtype != IL_BF16) return IL_E_ARG;
-  if (epi < EPI_STORE || epi > EPI_WGRAD || tile < 0 || tile > 3) return IL_E_ARG;
+  if (epi < EPI_STORE || epi > EPI_WGRAD || tile < 0 || tile > 4) return IL_E_ARG;
   if ((epi == EPI_BIAS || epi == EPI_BIAS_GELU || epi == EPI_BIAS_RES) && !bias) return IL_E_ARG;
   if ((epi == EPI_BIAS_RES && !res) || (epi == EPI_BIAS_GELU && !C2)) return IL_E_ARG;
   if (epi == EPI_GELU_BWD && (!aux || aux_wrap < 1)) return IL_E_ARG;
@@ -719,7 +747,10 @@ int il_test_gemm(int32_t dtype, const void *A, const void *B, int32_t M, int32_t
 
 int il_free(il_ctx *c) {
   if (!c) return IL_E_ARG;
-  for (auto &r : c->recs) { hipEventDestroy(r.e0); hipEventDestroy(r.e1); }
+  for (auto &r : c->recs) {
+    hipEventDestroy(r.e0); hipEventDestroy(r.e1);
+    hipEventDestroy(r.kt.start); hipEventDestroy(r.kt.stop);
+  }
   for (hipEvent_t e : c->ev_head) if (e) hipEventDestroy(e);
   if (c->ev_fork) hipEventDestroy(c->ev_fork);
   if (c->side) { hipStreamSynchronize(c->side); hipStreamDestroy(c->side); }

@@ -7,7 +7,7 @@ import pytest
 from paper_2010_04116_amd import binding as b, synth
 
 pytestmark = pytest.mark.gpu
-TILES = [1, 2, 3]
+TILES = [1, 2, 3, 4]
 
 
 def _bf16(a):
@@ -97,7 +97,7 @@ def test_k_tail_and_tiny_sizes(tile):
     run_case(40, 72, 72, 1, 1, 6, tile, seed=33)
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3])
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
 def test_multi_tile_shapes(tile):
     run_case(1024, 768, 512, 0, 1, 1, tile, seed=40)
     run_case(1024, 768, 512, 0, 0, 0, tile, seed=41)
