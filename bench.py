@@ -25,6 +25,14 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
+# HBM-side bytes per GEMM kernel launch (average over the launches of one step), from two
+# rocprofv3 --pmc runs of this script (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same
+# counter reads for a 256 MiB device-to-device copy (--calibration-copy-mib 256): see
+# profiles/traffic_small_bf16_n2.md.  bench.py cannot run the profiler on itself, so the
+# figure is carried here for the workload it was measured on and is null for any other.
+MEASURED_TRAFFIC = {
+}
+
 
 def minimal_flops(w):
     """Algorithmic flops of one step, not counting recomputation: per block forward
@@ -128,6 +136,7 @@ def measure(w, steps, warmup):
     flops = minimal_flops(w)
     gemm = [k for k in prof if k.startswith("gemm")]
     g_fl = sum(prof[k]["flops_per_step"] for k in gemm)
+    g_by = sum(prof[k]["bytes_per_step"] for k in gemm)
     g_n = sum(prof[k]["launches_per_step"] for k in gemm)
     if w.dtype == "bf16":
         # events attached to each MFMA GEMM dispatch: the kernel's own execution time
@@ -145,8 +154,10 @@ def measure(w, steps, warmup):
                      "kernel": "gemm_dma_kernel: every GEMM launch of one step (forward, dgrad, wgrad, head)"
                      if w.dtype == "bf16" else "gemm_simt_kernel: every GEMM launch of one step",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-                     "traffic": None, "launches_per_step": g_n, "avg_launch_ms": g_ms / max(g_n, 1),
-                     "algorithmic_gflop_per_launch": g_fl / max(g_n, 1) / 1e9, "timing": how},
+                     "traffic": MEASURED_TRAFFIC.get(f"{w.name}_{w.dtype}_n{w.n}"),
+                     "launches_per_step": g_n, "avg_launch_ms": g_ms / max(g_n, 1),
+                     "algorithmic_gflop_per_launch": g_fl / max(g_n, 1) / 1e9,
+                     "algorithmic_bytes_per_launch": g_by / max(g_n, 1), "timing": how},
         "kernels": {k: {"ms_per_step": round(v["ms_per_step"], 4), "launches": v["launches_per_step"],
                         "tflops": (v["flops_per_step"] / (v["ms_per_step"] * 1e-3) / 1e12)
                         if v["ms_per_step"] > 0 and v["flops_per_step"] else None,
@@ -175,6 +186,9 @@ def main():
     ap.add_argument("--also", default="medium",
                     help="comma-separated further workloads reported under other_workloads ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="first run one device-to-device copy of this many MiB (a kernel of known HBM "
+                         "traffic, against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); depthwise sharding "
@@ -183,6 +197,13 @@ def main():
         sys.exit("bench.py: launched with WORLD_SIZE > 1; this build runs on exactly one GPU")
 
     from paper_2010_04116_amd import synth
+    if a.calibration_copy_mib > 0:
+        import torch
+        src = torch.ones(a.calibration_copy_mib << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     w = synth.WORKLOADS[a.workload]
     if a.n:
         w = w.with_(n=a.n)

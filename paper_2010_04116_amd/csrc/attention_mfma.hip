@@ -142,22 +142,37 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16_t *__restrict__ 
     const int kv0 = kt * BKV;
     wait_vmcnt<0>();
     __syncthreads();  // tile kt is complete; every wavefront is done with tile kt-1
+    // A wavefront's LDS operations complete in issue order and a direct load is one of them:
+    // every fragment of tile kt is requested before the loads of tile kt+1 are issued, so the
+    // reads do not wait for data that is still on its way from memory.
+    const bool live = kv0 <= qw0 + 31;  // some key of the tile is visible to some query of this wavefront
+    bf16x8 kf[2][DH / 16], vf[2][2][DH / 32];
+    if (live) {
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int ks = 0; ks < DH / 16; ++ks) kf[a][ks] = Tile::rowfrag(sk, 32 * a, ks, lane);
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int bq = 0; bq < 2; ++bq)
+#pragma unroll
+          for (int dt = 0; dt < DH / 32; ++dt) vf[a][bq][dt] = Tile::trfrag(sv, 32 * a + 16 * bq, dt, lane);
+    }
     if (kt + 1 < nkv) {
       char *nk = smem + ((kt + 1) & 1) * STAGE;
       lk.issue(rs, nk, wave, kv0 + BKV, T);
       lv.issue(rs, nk + KT, wave, kv0 + BKV, T);
     }
-    if (kv0 <= qw0 + 31) {  // some key of the tile is visible to some query of this wavefront
+    if (live) {
       floatx16 s[2];
 #pragma unroll
       for (int a = 0; a < 2; ++a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[a][r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < DH / 16; ++ks) {
-          const bf16x8 kf = Tile::rowfrag(sk, 32 * a, ks, lane);
-          s[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks].v, s[a], 0, 0, 0);
-        }
+        for (int ks = 0; ks < DH / 16; ++ks)
+          s[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[a][ks], qf[ks].v, s[a], 0, 0, 0);
       }
       const bool diag = kv0 + BKV - 1 > qw0 || kv0 + BKV > T;
       float mx = kNegBig;
@@ -199,10 +214,8 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16_t *__restrict__ 
 #pragma unroll
           for (int e = 0; e < 4; ++e) pf.u[e] = pack2(s[a][8 * bq + 2 * e], s[a][8 * bq + 2 * e + 1]);
 #pragma unroll
-          for (int dt = 0; dt < DH / 32; ++dt) {
-            const bf16x8 vf = Tile::trfrag(sv, 32 * a + 16 * bq, dt, lane);
-            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf.v, oacc[dt], 0, 0, 0);
-          }
+          for (int dt = 0; dt < DH / 32; ++dt)
+            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[a][bq][dt], pf.v, oacc[dt], 0, 0, 0);
         }
     }
   }

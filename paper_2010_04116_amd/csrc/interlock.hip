@@ -285,6 +285,22 @@ hipError_t gemm(il_ctx *c, const GemmArgs &g) {
 inline const char *P(il_ctx *c, size_t off) { return (const char *)c->cfg.params + off * c->eb; }
 inline float *Gr(il_ctx *c, size_t off) { return (float *)c->cfg.grads + off; }
 
+// Algorithmic bytes of one GEMM: both operands once, the output once (and the operands the
+// epilogue adds: residual, pre-activation, or the accumulated-into output).
+double gemm_bytes(il_ctx *c, const GemmArgs &g) {
+  const double eb = c->eb, mn = (double)g.M * g.N;
+  double b = ((double)g.M * g.K + (double)g.K * g.N) * eb;
+  switch (g.epi) {
+    case EPI_BIAS_GELU: b += 2 * mn * eb; break;
+    case EPI_BIAS_RES: b += 2 * mn * 4; break;
+    case EPI_GELU_BWD: b += 2 * mn * eb; break;
+    case EPI_STORE_F32: b += mn * 4; break;
+    case EPI_WGRAD: b += mn * 4 * (g.beta ? 2 : 1); break;
+    default: b += mn * eb; break;
+  }
+  return b;
+}
+
 GemmArgs base_args() {
   GemmArgs g;
   memset(&g, 0, sizeof(g));
@@ -300,7 +316,7 @@ int linear_fwd(il_ctx *c, const void *x, size_t w_off, size_t b_off, int M, int 
   g.B = P(c, w_off); g.ldb = Nn; g.b_kmajor = 1;
   g.M = M; g.N = Nn; g.K = Kd; g.epi = epi; g.C = out; g.C2 = out2; g.ldc = Nn;
   g.bias = P(c, b_off); g.res = res;
-  Scope sc(c, KC_GEMM_FWD, 2.0 * M * Nn * Kd, 0);
+  Scope sc(c, KC_GEMM_FWD, 2.0 * M * Nn * Kd, gemm_bytes(c, g));
   IL_TRY(gemm(c, g));
   return IL_OK;
 }
@@ -312,7 +328,7 @@ int linear_dgrad(il_ctx *c, const void *dy, size_t w_off, int M, int Kin, int No
   g.A = dy; g.lda = Nout; g.a_kmajor = 0;
   g.B = P(c, w_off); g.ldb = Nout; g.b_kmajor = 0;
   g.M = M; g.N = Kin; g.K = Nout; g.epi = epi; g.C = out; g.ldc = Kin; g.aux = aux; g.aux_wrap = aux_wrap;
-  Scope sc(c, KC_GEMM_DGRAD, 2.0 * M * Kin * Nout, 0);
+  Scope sc(c, KC_GEMM_DGRAD, 2.0 * M * Kin * Nout, gemm_bytes(c, g));
   IL_TRY(gemm(c, g));
   return IL_OK;
 }
@@ -354,9 +370,12 @@ int linear_wgrad(il_ctx *c, const Run &cp, const void *x, const void *dy, int Ki
 
 int launch_wgrads(il_ctx *c, const GemmArgs *list, int n) {
   if (n == 0) return IL_OK;
-  double fl = 0;
-  for (int i = 0; i < n; ++i) fl += 2.0 * list[i].M * list[i].N * list[i].K;
-  Scope sc(c, KC_GEMM_WGRAD, fl, 0);
+  double fl = 0, by = 0;
+  for (int i = 0; i < n; ++i) {
+    fl += 2.0 * list[i].M * list[i].N * list[i].K;
+    by += gemm_bytes(c, list[i]);
+  }
+  Scope sc(c, KC_GEMM_WGRAD, fl, by);
   if (c->cfg.dtype == IL_F32) {
     for (int i = 0; i < n; ++i) IL_TRY(gemm_f32(list[i], c->stream));
   } else {
@@ -610,7 +629,7 @@ int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets,
     g.B = P(c, c->hoff[k - 1]); g.ldb = V; g.b_kmajor = 1;
     g.M = rows; g.N = V; g.K = d; g.epi = EPI_STORE; g.C = c->Z; g.ldc = V;
     {
-      Scope sc(c, KC_GEMM_HEAD, 2.0 * rows * V * d, 0);
+      Scope sc(c, KC_GEMM_HEAD, 2.0 * rows * V * d, gemm_bytes(c, g));
       IL_TRY(gemm(c, g));
     }
     {
@@ -622,7 +641,7 @@ int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets,
     g.B = P(c, c->hoff[k - 1]); g.ldb = V; g.b_kmajor = 0;
     g.M = rows; g.N = d; g.K = V; g.epi = EPI_STORE_F32; g.C = dx + (size_t)r0 * d; g.ldc = d;
     {
-      Scope sc(c, KC_GEMM_HEAD, 2.0 * rows * V * d, 0);
+      Scope sc(c, KC_GEMM_HEAD, 2.0 * rows * V * d, gemm_bytes(c, g));
       const int sp = choose_splits(c, rows, d, V);
       if (sp > 1) IL_TRY(gemm_bf16_splitk(g, sp, c->skws, c->stream));
       else IL_TRY(gemm(c, g));
@@ -633,7 +652,7 @@ int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets,
     g.M = d; g.N = V; g.K = rows; g.epi = EPI_WGRAD; g.C = Gr(c, c->hoff[k - 1]); g.ldc = V;
     g.beta = chunk > 0;
     {
-      Scope sc(c, KC_GEMM_HEAD, 2.0 * rows * V * d, 0);
+      Scope sc(c, KC_GEMM_HEAD, 2.0 * rows * V * d, gemm_bytes(c, g));
       IL_TRY(gemm(c, g));
     }
   }
