@@ -119,6 +119,81 @@ def test_small_bf16_full_step(n):
     assert np.all(np.abs(ref["losses"] - np.log(w.V)) < 0.5)     # uniform tokens: loss near ln V
 
 
+def _small_q():
+    return synth.Workload("small_q", "bf16", K=4, L=2, d=256, H=4, m=1024, V=2048, B=2, T=128, n=2)
+
+
+def test_losses_final_after_last_head_without_backward():
+    """Evaluation-style use: forwards and heads only.  The heads run on the library's internal
+    stream; the last head joins it, so synchronising the caller's stream is enough."""
+    w = _small_q()
+    params, x0, tgt = make_inputs(w, seed=4)
+    full = binding.run_step(w, params, x0, tgt)
+    st = binding.Step(w, binding.pack_params(w, params))
+    st.set_inputs(x0, tgt)
+    for k in range(1, w.K + 1):
+        binding.il_stage_forward(st.ctx, k, st.x[k - 1], st.x[k])
+        binding.il_head_xent(st.ctx, k, st.x[k], st.targets, st.losses[k - 1:])
+    st.stream.synchronize()
+    losses = st.losses.cpu().numpy().astype(np.float64)
+    head_grads = binding.unpack_grads(w, st.grads.cpu().numpy())["heads"]
+    st.close()
+    assert np.array_equal(losses, full["losses"])
+    for k in range(w.K):
+        assert np.array_equal(head_grads[k], full["head_grads"][k])
+
+
+def test_abandoned_step_does_not_disturb_the_next():
+    """A step that stops after two heads (their work still queued on the internal stream) is
+    followed at once by a complete step with other inputs on the same context."""
+    w = _small_q()
+    params, x0, tgt = make_inputs(w, seed=4)
+    _, x0b, tgtb = make_inputs(w, seed=9)
+    st = binding.Step(w, binding.pack_params(w, params))
+    st.set_inputs(x0b, tgtb)
+    for k in range(1, 3):
+        binding.il_stage_forward(st.ctx, k, st.x[k - 1], st.x[k])
+        binding.il_head_xent(st.ctx, k, st.x[k], st.targets, st.losses[k - 1:])
+    st.stream.synchronize()          # the caller's stream only; the heads may still be running
+    st.set_inputs(x0, tgt)
+    st.run()
+    got = st.results()
+    st.close()
+    ref = binding.run_step(w, params, x0, tgt)
+    assert np.array_equal(got["losses"], ref["losses"])
+    assert np.array_equal(got["dx0"], ref["dx0"])
+    for k in range(w.K):
+        assert np.array_equal(got["head_grads"][k], ref["head_grads"][k])
+
+
+def test_profiling_mode_same_results_and_sane_times():
+    w = _small_q()
+    params, x0, tgt = make_inputs(w, seed=4)
+    ref = binding.run_step(w, params, x0, tgt)
+    st = binding.Step(w, binding.pack_params(w, params), profile=True)
+    st.set_inputs(x0, tgt)
+    st.run()
+    got = st.results()
+    prof = binding.il_profile_read(st.ctx)
+    st.run()
+    prof2 = binding.il_profile_read(st.ctx)
+    st.close()
+    assert np.array_equal(got["losses"], ref["losses"])
+    assert np.array_equal(got["dx0"], ref["dx0"])
+    gemm = [k for k in prof if k.startswith("gemm")]
+    assert sorted(gemm) == ["gemm_dgrad", "gemm_fwd", "gemm_head", "gemm_wgrad"]
+    for k in gemm:
+        v = prof[k]
+        assert v["launches"] > 0 and v["flops"] > 0 and v["bytes"] > 0
+        assert 0 < v["kernel_ms"] <= v["ms"], (k, v)           # the kernel alone is inside its bracket
+        assert prof2[k]["launches"] == v["launches"]           # counters restart with each read
+    fwd_flops = 2.0 * w.N * (4 * w.d * w.d + 2 * w.d * w.m) * w.K * w.L
+    assert abs(prof["gemm_fwd"]["flops"] - fwd_flops) < 1e-6 * fwd_flops
+    for k in prof:
+        if not k.startswith("gemm"):
+            assert prof[k]["kernel_ms"] == 0.0
+
+
 # ------------------------------------------------ real-shape slices (bf16) ---------
 
 def test_medium_shape_one_component_and_head():
