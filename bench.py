@@ -167,7 +167,41 @@ def measure(w, steps, warmup):
                     for k, v in prof.items()},
         "losses": [float(x) for x in losses],
     }
+    res["optimizer"] = optimizer_line(w)
     return res, params, x0, tgt
+
+
+def optimizer_line(w, reps=10):
+    """The Adam update (App. B) over this workload's parameters: an HBM-bound kernel, timed on its own
+    with HIP events on the current stream and reported beside the step (it is not part of `value`,
+    which is the gradient step the metric names)."""
+    import torch
+    from paper_2010_04116_amd import binding
+    count = binding.param_count(w)
+    dev = "cuda:0"
+    master = torch.zeros(count, device=dev)
+    grads = torch.full((count,), 1e-3, device=dev)
+    m = torch.zeros(count, device=dev)
+    v = torch.zeros(count, device=dev)
+    bf = w.dtype == "bf16"
+    params = torch.zeros(count, dtype=torch.bfloat16, device=dev) if bf else master
+    st = torch.cuda.current_stream()
+    def go(step):
+        binding.il_adam_step(w.dtype, params, master if bf else None, grads, m, v, count, step,
+                             binding.il_lr_schedule(step, w.d, 4000), stream=st.cuda_stream)
+    go(1)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(st)
+    for i in range(reps):
+        go(2 + i)
+    e1.record(st)
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    per = 30 if bf else 28          # g, m, v, w read; m, v, w written; + the bf16 image
+    gbs = count * per / (ms * 1e-3) / 1e9
+    return {"kernel": "adam_step_kernel", "parameters": count, "ms": ms, "bound": "hbm", "achieved": gbs,
+            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "bytes_per_parameter": per}
 
 
 def config_of(w):

@@ -192,6 +192,32 @@ int il_test_gemm(int32_t dtype, const void *A, const void *B, int32_t M, int32_t
                  const void *bias, const float *res, const void *aux, int32_t aux_wrap, float scale,
                  int32_t beta, int32_t tile, void *stream);
 
+/* ---- optimiser step (App. B, training configuration of the Transformer runs) ------ */
+
+/*
+ * Learning rate d_model^-0.5 * min(step^-0.5, step * warmup_steps^-1.5), steps counted from 1
+ * (host function, no GPU work).  Returns 0 for step < 1, d_model < 1 or warmup_steps < 1.
+ */
+double il_lr_schedule(int64_t step, int32_t d_model, int32_t warmup_steps);
+
+/*
+ * One Adam update with bias correction over `count` parameters (the paper's setting is
+ * beta1 = 0.9, beta2 = 0.98, eps = 1e-9):
+ *   m <- beta1 m + (1-beta1) g,  v <- beta2 v + (1-beta2) g^2,
+ *   w <- w - lr * (m / (1-beta1^step)) / (sqrt(v / (1-beta2^step)) + eps).
+ * No weight decay, no clipping.  All pointers are device pointers owned by the caller; the
+ * work is enqueued on `stream` (hipStream_t, NULL = default stream).
+ *   dtype IL_F32 : params is the fp32 weight buffer, updated in place; master must be NULL.
+ *   dtype IL_BF16: master is the fp32 copy of the weights (updated in place) and params
+ *                  receives its bfloat16 image (round to nearest even).
+ * grads, m, v: fp32 [count] in the flat parameter order described above; m and v start at zero
+ * and are updated in place; step >= 1 is the number of this update.  fp32 buffers must be 16-byte
+ * aligned (bf16 params 8-byte): IL_E_SHAPE otherwise.  IL_E_ARG for NULL pointers, step < 1,
+ * betas outside [0,1), negative eps or lr, or a master that does not match dtype.
+ */
+int il_adam_step(int32_t dtype, void *params, float *master, const float *grads, float *m, float *v,
+                 size_t count, int64_t step, float lr, float beta1, float beta2, float eps, void *stream);
+
 /* Static string for a status code. */
 const char *il_status_string(int status);
 

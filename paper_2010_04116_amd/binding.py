@@ -22,7 +22,8 @@ IL_OK, IL_E_ARG, IL_E_SHAPE, IL_E_STATE, IL_E_WORKSPACE, IL_E_HIP = 0, -1, -2, -
 IL_F32, IL_BF16 = 0, 1
 ROUTES = {"window_sum": 0, "far_head": 1, "mean_local_far": 2}
 SYMBOLS = ("il_init", "il_stage_forward", "il_head_xent", "il_stage_backward_nwise", "il_free",
-           "il_routing_plan", "il_profile_read", "il_status_string", "il_test_gemm")
+           "il_routing_plan", "il_profile_read", "il_status_string", "il_test_gemm", "il_lr_schedule",
+           "il_adam_step")
 
 
 class il_config(C.Structure):
@@ -62,10 +63,15 @@ def load():
                                     C.POINTER(C.c_double)]
     lib.il_test_gemm.argtypes = [i32, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, vp, i32, vp, vp, vp,
                                  i32, C.c_float, i32, i32, vp]
+    lib.il_lr_schedule.argtypes = [C.c_int64, i32, i32]
+    lib.il_lr_schedule.restype = C.c_double
+    lib.il_adam_step.argtypes = [i32, vp, vp, vp, vp, vp, C.c_size_t, C.c_int64, C.c_float, C.c_float, C.c_float,
+                                 C.c_float, vp]
     lib.il_status_string.argtypes = [C.c_int]
     lib.il_status_string.restype = C.c_char_p
     for name in SYMBOLS:
-        getattr(lib, name).restype = getattr(lib, name).restype if name == "il_status_string" else C.c_int
+        if name not in ("il_status_string", "il_lr_schedule"):
+            getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
 
@@ -165,6 +171,20 @@ def il_profile_read(ctx) -> Dict[str, dict]:
         raise InterlockError(cnt, "il_profile_read")
     return {names[i].decode(): dict(launches=n[i], ms=ms[i], flops=fl[i], bytes=by[i], kernel_ms=kms[i])
             for i in range(cnt)}
+
+
+def il_lr_schedule(step: int, d_model: int, warmup_steps: int = 4000) -> float:
+    return float(load().il_lr_schedule(step, d_model, warmup_steps))
+
+
+def il_adam_step(dtype, params, master, grads, m, v, count: int, step: int, lr: float,
+                 beta1: float = 0.9, beta2: float = 0.98, eps: float = 1e-9, stream=None):
+    """Device tensors (or raw pointers) in, one fused Adam update enqueued on `stream`."""
+    def p(x):
+        return None if x is None else (x.data_ptr() if hasattr(x, "data_ptr") else x)
+    dt = {"f32": IL_F32, "bf16": IL_BF16}[dtype] if isinstance(dtype, str) else dtype
+    _check(load().il_adam_step(dt, p(params), p(master), p(grads), p(m), p(v), count, step, lr, beta1, beta2,
+                               eps, stream), "il_adam_step")
 
 
 # --------------------------------------------------------------------------------------

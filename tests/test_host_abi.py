@@ -99,3 +99,29 @@ def test_pack_unpack_roundtrip():
         for name in synth.BLOCK_TENSORS:
             assert np.array_equal(back["components"][k][0][name], p["components"][k][0][name])
         assert np.array_equal(back["heads"][k], p["heads"][k])
+
+
+def test_lr_schedule_and_adam_misuse_without_a_gpu():
+    """il_lr_schedule is a host function; il_adam_step rejects bad arguments before any launch."""
+    import math
+    from oracle import adam as A
+    for step in (1, 7, 3999, 4000, 4001, 123456):
+        assert binding.il_lr_schedule(step, 1024, 4000) == pytest.approx(A.lr_schedule(step, 1024, 4000), rel=1e-14)
+    assert binding.il_lr_schedule(4000, 1024, 4000) == pytest.approx(1.0 / (32.0 * math.sqrt(4000.0)), rel=1e-14)
+    assert binding.il_lr_schedule(0, 1024, 4000) == 0.0
+    lib = binding.load()
+    fake = C.c_void_p(4096)
+    ok = (binding.IL_F32, fake, None, fake, fake, fake, 64, 1, 0.1, 0.9, 0.98, 1e-9, None)
+    def call(**kw):
+        names = ("dtype", "params", "master", "grads", "m", "v", "count", "step", "lr", "beta1", "beta2", "eps", "stream")
+        a = dict(zip(names, ok)); a.update(kw)
+        return lib.il_adam_step(*[a[n] for n in names])
+    assert call(count=0) == binding.IL_OK                       # nothing to do, nothing launched
+    assert call(dtype=7) == binding.IL_E_ARG
+    assert call(params=None) == binding.IL_E_ARG
+    assert call(step=0) == binding.IL_E_ARG
+    assert call(beta2=1.0) == binding.IL_E_ARG
+    assert call(lr=-0.1) == binding.IL_E_ARG
+    assert call(master=fake) == binding.IL_E_ARG                # fp32 mode takes no master copy
+    assert call(dtype=binding.IL_BF16) == binding.IL_E_ARG      # bf16 mode needs one
+    assert call(grads=C.c_void_p(4100)) == binding.IL_E_SHAPE   # misaligned
