@@ -148,6 +148,11 @@ hipError_t colsum_final_multi(const ColsumJobs &jobs, hipStream_t s);
 // fence, which on this multi-XCD part writes back the L2 and costs far more than a launch.)
 hipError_t sum_colsum(int dtype, const void *Y, int N, int cols, int ld, int ns, StreamWeights sw, void *ysum,
                       float *partials, int *nblk, hipStream_t s);
+// Several such reductions over the same number of rows in one launch (grid.z selects the job).
+struct SumColsumJob { const void *Y; int N, cols, ldy, ns; StreamWeights sw; void *ysum; float *partials; };
+constexpr int kMaxSumColsumJobs = 2;
+struct SumColsumJobs { int count; SumColsumJob job[kMaxSumColsumJobs]; };
+hipError_t sum_colsum_multi(int dtype, const SumColsumJobs &jobs, int *nblk, hipStream_t s);
 int colsum_max_blocks();
 // G[i] = (accumulate ? G[i] : 0) + src[i]; Gb[i] = T(G[i])
 hipError_t stream_inject(int dtype, const float *src, float *G, void *Gb, size_t count, int accumulate,

@@ -175,6 +175,8 @@ struct il_ctx {
   std::vector<BlockSave> save;     // K*L
   float *G; char *Gb;              // stream slots [nslots][N,d]
   char *DU, *DH, *DQKV, *YS[4]; float *dsum, *partials[6], *skws; size_t skws_floats; ColsumJobs jobs;
+  SumColsumJobs pending; float *pending_out[kMaxSumColsumJobs]; int pending_acc[kMaxSumColsumJobs];
+  double pending_bytes = 0;
   char *xb, *Z; float *rowloss, *dxh;
   int Nc;
   std::vector<char> fwd_done, head_done, bwd_done;
@@ -333,6 +335,24 @@ int linear_dgrad(il_ctx *c, const void *dy, size_t w_off, int M, int Kin, int No
   return IL_OK;
 }
 
+// Launch the queued stream-sum / column-sum reductions (at most two, one launch) and register their
+// second stages.  Must run before a queued operand is overwritten (LayerNorm backward rewrites the
+// gradient stream) and before the block's final column reduction.
+int flush_colsums(il_ctx *c) {
+  if (c->pending.count == 0) return IL_OK;
+  int nblk = 0;
+  {
+    Scope sc(c, KC_COLSUM, 0, c->pending_bytes);
+    IL_TRY(sum_colsum_multi(c->cfg.dtype, c->pending, &nblk, c->stream));
+  }
+  for (int i = 0; i < c->pending.count; ++i)
+    c->jobs.job[c->jobs.count++] = ColsumJob{c->pending.job[i].partials, nblk, c->pending.job[i].cols,
+                                             c->pending_out[i], c->pending_acc[i]};
+  c->pending.count = 0;
+  c->pending_bytes = 0;
+  return IL_OK;
+}
+
 // dW[Kin,Nout] = x[N,Kin]^T (sum_s w_s dy_s[N,Nout]);  db = column sums of the same weighted sum.
 // The streams are summed first (linearity of the weight gradient), fused with the first stage of
 // the bias-gradient column sum.  The GEMM itself is only described here (`out`); the four weight
@@ -345,19 +365,25 @@ int linear_wgrad(il_ctx *c, const Run &cp, const void *x, const void *dy, int Ki
   const bool in_place = cp.nweighted == 1 && cp.wscale == 1.f && !keep;
   const char *dys = in_place ? (const char *)dy + (size_t)cp.first_weighted * c->N * Nout * c->eb : c->YS[slot];
   {
-    StreamWeights sw;
-    memset(&sw, 0, sizeof(sw));
-    int nblk = 0;
-    Scope sc(c, KC_COLSUM, 0, (double)(in_place ? 1 : cp.nweighted + 1) * c->N * Nout * c->eb);
+    // queued: two of a block's four reductions are ready at the same point of the backward and
+    // share one launch (flush_colsums)
+    SumColsumJob jb;
+    memset(&jb, 0, sizeof(jb));
+    jb.N = c->N; jb.cols = Nout; jb.ldy = Nout; jb.partials = c->partials[slot];
     if (in_place) {
-      sw.w[0] = 1.f;
-      IL_TRY(sum_colsum(c->cfg.dtype, dys, c->N, Nout, Nout, 1, sw, nullptr, c->partials[slot], &nblk, c->stream));
+      jb.Y = dys; jb.ns = 1; jb.sw.w[0] = 1.f; jb.ysum = nullptr;
     } else {
-      memcpy(sw.w, cp.wt, sizeof(sw.w));
-      IL_TRY(sum_colsum(c->cfg.dtype, dy, c->N, Nout, Nout, cp.cnt, sw, c->YS[slot], c->partials[slot], &nblk,
-                        c->stream));
+      jb.Y = dy; jb.ns = cp.cnt; memcpy(jb.sw.w, cp.wt, sizeof(jb.sw.w)); jb.ysum = c->YS[slot];
     }
-    c->jobs.job[c->jobs.count++] = ColsumJob{c->partials[slot], nblk, Nout, Gr(c, b_off), cp.acc};
+    c->pending.job[c->pending.count] = jb;
+    c->pending_out[c->pending.count] = Gr(c, b_off);
+    c->pending_acc[c->pending.count] = cp.acc;
+    c->pending_bytes += (double)(in_place ? 1 : cp.nweighted + 1) * c->N * Nout * c->eb;
+    ++c->pending.count;
+    if (c->pending.count == kMaxSumColsumJobs) {
+      const int rc = flush_colsums(c);
+      if (rc) return rc;
+    }
   }
   GemmArgs g = base_args();
   g.A = x; g.lda = Kin; g.a_kmajor = 1;
@@ -449,11 +475,14 @@ int block_backward(il_ctx *c, const Run &cp, const BlockOff &b, const BlockSave 
   int rc, nw = 0;
   GemmArgs wg[4];
   c->jobs.count = 0;
+  c->pending.count = 0;
+  c->pending_bytes = 0;
   // MLP
   if ((rc = linear_dgrad(c, Gb, b.w_fc2, S, m, d, EPI_GELU_BWD, c->DU, s.u, N))) return rc;
   if ((rc = linear_wgrad(c, cp, s.gl, Gb, m, d, b.w_fc2, b.b_fc2, 0, true, wg, &nw))) return rc;
   if ((rc = linear_wgrad(c, cp, s.h2, c->DU, d, m, b.w_fc1, b.b_fc1, 1, false, wg, &nw))) return rc;
   if ((rc = linear_dgrad(c, c->DU, b.w_fc1, S, d, m, EPI_STORE, c->DH, nullptr, 0))) return rc;
+  if ((rc = flush_colsums(c))) return rc;  // the stream is about to change
   if ((rc = ln_bwd(c, cp, c->DH, s.a, s.st2, b.ln2_g, G, Gb, 4))) return rc;
   // attention
   if ((rc = linear_wgrad(c, cp, s.o, Gb, d, d, b.w_o, b.b_o, 2, true, wg, &nw))) return rc;
@@ -461,6 +490,7 @@ int block_backward(il_ctx *c, const Run &cp, const BlockOff &b, const BlockSave 
   if ((rc = attention_bwd(c, s, c->DH, cp.cnt, c->DQKV))) return rc;
   if ((rc = linear_wgrad(c, cp, s.h1, c->DQKV, d, 3 * d, b.w_qkv, b.b_qkv, 3, false, wg, &nw))) return rc;
   if ((rc = linear_dgrad(c, c->DQKV, b.w_qkv, S, d, 3 * d, EPI_STORE, c->DH, nullptr, 0))) return rc;
+  if ((rc = flush_colsums(c))) return rc;
   if ((rc = ln_bwd(c, cp, c->DH, s.xs, s.st1, b.ln1_g, G, Gb, 5))) return rc;
   {  // second stage of the six column reductions (four bias gradients, two LayerNorm gain/bias pairs)
     Scope sc(c, KC_COLSUM, 0, 0);

@@ -14,11 +14,16 @@ constexpr int kColBlocksY = 64;   // row splits of the first stage
 // column sums (the bias gradient).  V = 8: grid (ceil(cols/256), nby), block = 32 column groups
 // of 8 x 8 row lanes, 16-byte accesses (cols % 8 == 0).  V = 1: block = 64 columns x 4 row lanes.
 template <typename T, int V>
-__global__ __launch_bounds__(256) void sum_colsum_kernel(const T *__restrict__ Y, int N, int cols, int ldy, int ns,
-                                                         StreamWeights sw, T *__restrict__ ysum,
-                                                         float *__restrict__ partials) {
+__global__ __launch_bounds__(256) void sum_colsum_kernel(SumColsumJobs jobs) {
   constexpr int CG = V == 8 ? 32 : 64, RL = 256 / CG;
   __shared__ float red[RL][CG * V];
+  const SumColsumJob &jb = jobs.job[blockIdx.z];   // grid.z selects the job
+  const T *__restrict__ Y = (const T *)jb.Y;
+  T *__restrict__ ysum = (T *)jb.ysum;
+  float *__restrict__ partials = jb.partials;
+  const int N = jb.N, cols = jb.cols, ldy = jb.ldy, ns = jb.ns;
+  const StreamWeights &sw = jb.sw;
+  if ((int)blockIdx.x * CG * V >= cols) return;  // uniform: this job is narrower than the widest one
   const int tx = threadIdx.x % CG, ty = threadIdx.x / CG;
   const int c = (blockIdx.x * CG + tx) * V;
   const int per = (N + gridDim.y - 1) / gridDim.y;
@@ -149,22 +154,37 @@ inline int grid_for(size_t count) {
 }  // namespace
 
 int colsum_max_blocks() { return kColBlocksY; }
-hipError_t sum_colsum(int dtype, const void *Y, int N, int cols, int ldy, int ns, StreamWeights sw, void *ysum,
-                      float *partials, int *nblk, hipStream_t s) {
+hipError_t sum_colsum_multi(int dtype, const SumColsumJobs &jobs, int *nblk, hipStream_t s) {
+  if (jobs.count < 1 || jobs.count > kMaxSumColsumJobs) return hipErrorInvalidValue;
+  const int N = jobs.job[0].N;
   int nby = (N + 63) / 64;
   if (nby > kColBlocksY) nby = kColBlocksY;
   if (nby < 1) nby = 1;
   *nblk = nby;
+  int maxc = 0;
+  bool vec = dtype != 0;
+  for (int i = 0; i < jobs.count; ++i) {
+    const SumColsumJob &j = jobs.job[i];
+    if (j.N != N) return hipErrorInvalidValue;  // the jobs of one launch share the row split
+    maxc = j.cols > maxc ? j.cols : maxc;
+    vec = vec && (j.cols & 7) == 0 && (j.ldy & 7) == 0;
+  }
   if (dtype == 0)
-    hipLaunchKernelGGL((sum_colsum_kernel<float, 1>), dim3((cols + 63) / 64, nby), dim3(256), 0, s,
-                       (const float *)Y, N, cols, ldy, ns, sw, (float *)ysum, partials);
-  else if ((cols & 7) == 0 && (ldy & 7) == 0)
-    hipLaunchKernelGGL((sum_colsum_kernel<bf16_t, 8>), dim3((cols + 255) / 256, nby), dim3(256), 0, s,
-                       (const bf16_t *)Y, N, cols, ldy, ns, sw, (bf16_t *)ysum, partials);
+    hipLaunchKernelGGL((sum_colsum_kernel<float, 1>), dim3((maxc + 63) / 64, nby, jobs.count), dim3(256), 0, s, jobs);
+  else if (vec)
+    hipLaunchKernelGGL((sum_colsum_kernel<bf16_t, 8>), dim3((maxc + 255) / 256, nby, jobs.count), dim3(256), 0, s,
+                       jobs);
   else
-    hipLaunchKernelGGL((sum_colsum_kernel<bf16_t, 1>), dim3((cols + 63) / 64, nby), dim3(256), 0, s,
-                       (const bf16_t *)Y, N, cols, ldy, ns, sw, (bf16_t *)ysum, partials);
+    hipLaunchKernelGGL((sum_colsum_kernel<bf16_t, 1>), dim3((maxc + 63) / 64, nby, jobs.count), dim3(256), 0, s, jobs);
   return hipGetLastError();
+}
+
+hipError_t sum_colsum(int dtype, const void *Y, int N, int cols, int ldy, int ns, StreamWeights sw, void *ysum,
+                      float *partials, int *nblk, hipStream_t s) {
+  SumColsumJobs jobs;
+  jobs.count = 1;
+  jobs.job[0] = SumColsumJob{Y, N, cols, ldy, ns, sw, ysum, partials};
+  return sum_colsum_multi(dtype, jobs, nblk, s);
 }
 
 // Several second stages in one launch: grid.y selects the job.
