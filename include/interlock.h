@@ -13,12 +13,15 @@
  * library allocates no device memory: parameters, gradients, the workspace and the
  * stream come from the caller.  All work is enqueued asynchronously, ordered with
  * il_config.stream: the caller synchronises that stream before reading results.  (The
- * context owns one further non-blocking stream and a few events, on which il_head_xent
- * runs concurrently with the next component's forward; il_stage_backward_nwise and
- * il_head_xent(K), the step's last head, join it back into il_config.stream, so the caller
- * never sees it.  A loss or a head gradient is therefore final on il_config.stream once the
- * call that joins it has been enqueued; until then the x_k and targets buffers handed to
- * il_head_xent must not be overwritten.)
+ * context owns one further non-blocking stream and a few events.  il_head_xent runs on it,
+ * concurrently with the next component's forward; il_head_xent(K), the step's last head,
+ * and il_stage_backward_nwise join it back into il_config.stream.  The tail of every
+ * block's backward - bias and LayerNorm gradient reductions, weight gradients - runs on it
+ * too, concurrently with the next block; il_stage_backward_nwise(1), the step's last call,
+ * joins it back.  So the caller never sees that stream: losses and head gradients are
+ * final on il_config.stream once il_head_xent(K) has been enqueued, component gradients
+ * once il_stage_backward_nwise(1) has been; until then the x_k and targets buffers handed
+ * to il_head_xent must not be overwritten.)
  * Every function returns an il_status; nothing is printed and nothing aborts.
  *
  * Components and heads are numbered 1..K as in the paper.
@@ -140,7 +143,8 @@ int il_head_xent(il_ctx *ctx, int32_t k, const float *x_k, const int32_t *target
  * component's parameter gradient receives sum_j w[k][j] * dL_j/dtheta_k; streams whose
  * lowest credited component is k stop here (stop-gradient at the window edge).
  * Call for k = K, K-1, ..., 1, after il_head_xent(j) for every head j >= k that is live
- * at k.  dx0_out: for k == 1, optional device fp32 [N, d_model] receiving
+ * at k.  The gradients of all components are final on il_config.stream after the call for
+ * k = 1 (see the note on the internal stream above).  dx0_out: for k == 1, optional device fp32 [N, d_model] receiving
  * sum_j w[1][j] * dL_j/dx_0 (for the caller's embedding gradient); NULL to skip; ignored
  * for k > 1.
  */

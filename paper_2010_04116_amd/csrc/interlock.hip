@@ -175,6 +175,12 @@ struct il_ctx {
   std::vector<BlockSave> save;     // K*L
   float *G; char *Gb;              // stream slots [nslots][N,d]
   char *DU, *DH, *DQKV, *YS[4]; float *dsum, *partials[6], *skws; size_t skws_floats; ColsumJobs jobs;
+  // The end of a block's backward (final column sums, the four weight gradients) runs on the side
+  // stream while the main stream goes on with the next block: its inputs are double-buffered.
+  char *YS2[2][4]; float *partials2[2][6];
+  int bparity = 0;
+  hipEvent_t ev_blk_ready[2] = {nullptr, nullptr}, ev_blk_done[2] = {nullptr, nullptr};
+  char blk_pending[2] = {0, 0};
   SumColsumJobs pending; float *pending_out[kMaxSumColsumJobs]; int pending_acc[kMaxSumColsumJobs];
   double pending_bytes = 0;
   char *xb, *Z; float *rowloss, *dxh;
@@ -234,15 +240,20 @@ size_t layout_workspace(il_ctx *c, void *base) {
   c->DH = (char *)cv.take(S * d * eb);
   c->DQKV = (char *)cv.take(S * 3 * d * eb);
   c->dsum = (float *)cv.take(S * H * 4);
-  c->YS[0] = (char *)cv.take(N * d * eb);      // summed dY of FC2
-  c->YS[1] = (char *)cv.take(N * m * eb);      // FC1
-  c->YS[2] = (char *)cv.take(N * d * eb);      // attention output projection
-  c->YS[3] = (char *)cv.take(N * 3 * d * eb);  // QKV
+  for (int p = 0; p < 2; ++p) {
+    c->YS2[p][0] = (char *)cv.take(N * d * eb);      // summed dY of FC2
+    c->YS2[p][1] = (char *)cv.take(N * m * eb);      // FC1
+    c->YS2[p][2] = (char *)cv.take(N * d * eb);      // attention output projection
+    c->YS2[p][3] = (char *)cv.take(N * 3 * d * eb);  // QKV
+  }
+  for (int i = 0; i < 4; ++i) c->YS[i] = c->YS2[0][i];
   c->skws_floats = (size_t)kMaxBatch * c->Nc * d;
   c->skws = (float *)cv.take(c->skws_floats * 4);
   size_t pcols = std::max((size_t)3 * d, m);
   size_t pbytes = std::max((size_t)ln_backward_max_blocks() * 2 * d, (size_t)colsum_max_blocks() * pcols) * 4;
-  for (int i = 0; i < 6; ++i) c->partials[i] = (float *)cv.take(pbytes);
+  for (int p = 0; p < 2; ++p)
+    for (int i = 0; i < 6; ++i) c->partials2[p][i] = (float *)cv.take(pbytes);
+  for (int i = 0; i < 6; ++i) c->partials[i] = c->partials2[0][i];
   c->jobs.count = 0;
   c->xb = (char *)cv.take(N * d * eb);
   c->Z = (char *)cv.take((size_t)c->Nc * c->V * eb);
@@ -335,6 +346,31 @@ int linear_dgrad(il_ctx *c, const void *dy, size_t w_off, int M, int Kin, int No
   return IL_OK;
 }
 
+// The context's second stream (non-blocking, default priority) and the events that tie it to the
+// caller's stream; created on first use.
+int ensure_side(il_ctx *c) {
+  if (c->side) return IL_OK;
+  IL_TRY(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
+  IL_TRY(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
+  c->ev_head.assign(c->K + 1, nullptr);
+  for (int j = 1; j <= c->K; ++j) IL_TRY(hipEventCreateWithFlags(&c->ev_head[j], hipEventDisableTiming));
+  for (int p = 0; p < 2; ++p) {
+    IL_TRY(hipEventCreateWithFlags(&c->ev_blk_ready[p], hipEventDisableTiming));
+    IL_TRY(hipEventCreateWithFlags(&c->ev_blk_done[p], hipEventDisableTiming));
+  }
+  return IL_OK;
+}
+
+// The caller's stream waits for every block tail still running on the side stream.
+int join_block_tails(il_ctx *c) {
+  for (int p = 0; p < 2; ++p)
+    if (c->blk_pending[p]) {
+      IL_TRY(hipStreamWaitEvent(c->main_stream, c->ev_blk_done[p], 0));
+      c->blk_pending[p] = 0;
+    }
+  return IL_OK;
+}
+
 // Launch the queued stream-sum / column-sum reductions (at most two, one launch) and register their
 // second stages.  Must run before a queued operand is overwritten (LayerNorm backward rewrites the
 // gradient stream) and before the block's final column reduction.
@@ -362,7 +398,9 @@ int flush_colsums(il_ctx *c) {
 int linear_wgrad(il_ctx *c, const Run &cp, const void *x, const void *dy, int Kin, int Nout, size_t w_off,
                  size_t b_off, int slot, bool keep, GemmArgs *out, int *nout) {
   if (cp.nweighted == 0) return IL_OK;  // pass-through streams only: nothing is credited
-  const bool in_place = cp.nweighted == 1 && cp.wscale == 1.f && !keep;
+  // (with the block tail on the side stream every operand is materialised: the scratch it would
+  // be read from is rewritten by the next block meanwhile)
+  const bool in_place = cp.nweighted == 1 && cp.wscale == 1.f && !keep && c->cfg.profile;
   const char *dys = in_place ? (const char *)dy + (size_t)cp.first_weighted * c->N * Nout * c->eb : c->YS[slot];
   {
     // queued: two of a block's four reductions are ready at the same point of the backward and
@@ -477,6 +515,18 @@ int block_backward(il_ctx *c, const Run &cp, const BlockOff &b, const BlockSave 
   c->jobs.count = 0;
   c->pending.count = 0;
   c->pending_bytes = 0;
+  const bool async_tail = !c->cfg.profile;
+  const int par = c->bparity;
+  if (async_tail) {
+    if ((rc = ensure_side(c))) return rc;
+    c->bparity ^= 1;
+    if (c->blk_pending[par]) {  // the tail that last used this half of the buffers
+      IL_TRY(hipStreamWaitEvent(c->stream, c->ev_blk_done[par], 0));
+      c->blk_pending[par] = 0;
+    }
+    for (int i = 0; i < 4; ++i) c->YS[i] = c->YS2[par][i];
+    for (int i = 0; i < 6; ++i) c->partials[i] = c->partials2[par][i];
+  }
   // MLP
   if ((rc = linear_dgrad(c, Gb, b.w_fc2, S, m, d, EPI_GELU_BWD, c->DU, s.u, N))) return rc;
   if ((rc = linear_wgrad(c, cp, s.gl, Gb, m, d, b.w_fc2, b.b_fc2, 0, true, wg, &nw))) return rc;
@@ -492,12 +542,30 @@ int block_backward(il_ctx *c, const Run &cp, const BlockOff &b, const BlockSave 
   if ((rc = linear_dgrad(c, c->DQKV, b.w_qkv, S, d, 3 * d, EPI_STORE, c->DH, nullptr, 0))) return rc;
   if ((rc = flush_colsums(c))) return rc;
   if ((rc = ln_bwd(c, cp, c->DH, s.xs, s.st1, b.ln1_g, G, Gb, 5))) return rc;
-  {  // second stage of the six column reductions (four bias gradients, two LayerNorm gain/bias pairs)
+  // The block's tail - second stage of the six column reductions (four bias gradients, two LayerNorm
+  // gain/bias pairs) and the four weight gradients in one launch - depends on nothing later and nothing
+  // later depends on it: it runs on the side stream, concurrently with the next block's backward.
+  struct StreamSwap {
+    il_ctx *c; bool on;
+    ~StreamSwap() { if (on) c->stream = c->main_stream; }
+  } swap{c, false};
+  if (async_tail) {
+    IL_TRY(hipEventRecord(c->ev_blk_ready[par], c->main_stream));
+    IL_TRY(hipStreamWaitEvent(c->side, c->ev_blk_ready[par], 0));
+    c->stream = c->side;
+    swap.on = true;
+  }
+  {
     Scope sc(c, KC_COLSUM, 0, 0);
     IL_TRY(colsum_final_multi(c->jobs, c->stream));
     c->jobs.count = 0;
   }
-  return launch_wgrads(c, wg, nw);
+  if ((rc = launch_wgrads(c, wg, nw))) return rc;
+  if (async_tail) {
+    IL_TRY(hipEventRecord(c->ev_blk_done[par], c->side));
+    c->blk_pending[par] = 1;
+  }
+  return IL_OK;
 }
 
 int validate(const il_config *cfg) {
@@ -606,6 +674,7 @@ int il_stage_forward(il_ctx *c, int32_t k, const float *x_in, float *x_out) {
         if (hipStreamWaitEvent(c->stream, c->ev_head[j], 0) != hipSuccess) return IL_E_HIP;
         c->head_pending[j] = 0;
       }
+    { const int rc = join_block_tails(c); if (rc) return rc; }  // ... or weight gradients of its backward
   } else if (!c->fwd_done[k - 1]) {
     return IL_E_STATE;
   }
@@ -635,12 +704,7 @@ int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets,
     ~StreamSwap() { if (on) c->stream = c->main_stream; }
   } swap{c, false};
   if (!c->cfg.profile) {
-    if (!c->side) {
-      IL_TRY(hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking));
-      IL_TRY(hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming));
-      c->ev_head.assign(c->K + 1, nullptr);
-      for (int j = 1; j <= c->K; ++j) IL_TRY(hipEventCreateWithFlags(&c->ev_head[j], hipEventDisableTiming));
-    }
+    { const int rc = ensure_side(c); if (rc) return rc; }
     IL_TRY(hipEventRecord(c->ev_fork, c->main_stream));
     IL_TRY(hipStreamWaitEvent(c->side, c->ev_fork, 0));
     c->stream = c->side;
@@ -742,6 +806,8 @@ int il_stage_backward_nwise(il_ctx *c, int32_t k, float *dx0_out) {
     }
   }
   c->bwd_done[k] = 1;
+  // the step's last backward call joins the block tails still running on the side stream
+  if (k == 1) { const int rc = join_block_tails(c); if (rc) return rc; }
   return IL_OK;
 }
 
@@ -796,13 +862,18 @@ int il_test_gemm(int32_t dtype, const void *A, const void *B, int32_t M, int32_t
 
 int il_free(il_ctx *c) {
   if (!c) return IL_E_ARG;
+  if (c->side) hipStreamSynchronize(c->side);  // nothing of this context is left running on it
   for (auto &r : c->recs) {
     hipEventDestroy(r.e0); hipEventDestroy(r.e1);
     hipEventDestroy(r.kt.start); hipEventDestroy(r.kt.stop);
   }
   for (hipEvent_t e : c->ev_head) if (e) hipEventDestroy(e);
   if (c->ev_fork) hipEventDestroy(c->ev_fork);
-  if (c->side) { hipStreamSynchronize(c->side); hipStreamDestroy(c->side); }
+  for (int p = 0; p < 2; ++p) {
+    if (c->ev_blk_ready[p]) hipEventDestroy(c->ev_blk_ready[p]);
+    if (c->ev_blk_done[p]) hipEventDestroy(c->ev_blk_done[p]);
+  }
+  if (c->side) hipStreamDestroy(c->side);
   delete c;
   return IL_OK;
 }
