@@ -86,6 +86,51 @@ template <typename T> struct Vec<T, 1> {
   static __device__ inline void store(T *p, const float (&o)[1]) { st<T>(p, o[0]); }
 };
 
+// Forward with 16-byte accesses for d = 256 J: a lane owns columns (lane + 64 j) * 4 + (0..3), j < J.
+template <typename T, int J>
+__global__ __launch_bounds__(256) void ln_fwd_vec_kernel(const float *__restrict__ x, const T *__restrict__ gamma,
+                                                         const T *__restrict__ beta, float eps, int rows,
+                                                         T *__restrict__ y, float *__restrict__ stats,
+                                                         float *__restrict__ xcopy) {
+  constexpr int d = 256 * J;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = blockIdx.x * kWaves + wave;
+  if (row >= rows) return;
+  const float *xr = x + (size_t)row * d;
+  float v[J][4];
+  float s = 0.f;
+#pragma unroll
+  for (int j = 0; j < J; ++j) {
+    Vec<float, 4>::load(xr + (lane + 64 * j) * 4, v[j]);
+    s += (v[j][0] + v[j][1]) + (v[j][2] + v[j][3]);
+  }
+  const float mean = wave_sum(s) * (1.f / d);
+  float q = 0.f;
+#pragma unroll
+  for (int j = 0; j < J; ++j)
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float t = v[j][e] - mean;
+      q += t * t;
+    }
+  const float rstd = rsqrtf(wave_sum(q) * (1.f / d) + eps);
+#pragma unroll
+  for (int j = 0; j < J; ++j) {
+    const int c = (lane + 64 * j) * 4;
+    float g[4], b[4], o[4];
+    Vec<T, 4>::load(gamma + c, g);
+    Vec<T, 4>::load(beta + c, b);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = (v[j][e] - mean) * rstd * g[e] + b[e];
+    Vec<T, 4>::store(y + (size_t)row * d + c, o);
+    if (xcopy) Vec<float, 4>::store(xcopy + (size_t)row * d + c, v[j]);
+  }
+  if (lane == 0) {
+    stats[2 * row] = mean;
+    stats[2 * row + 1] = rstd;
+  }
+}
+
 // Lane owns columns (lane + 64 j) * V + (0..V-1), j < J.
 template <typename T, int V, int J>
 __global__ __launch_bounds__(256) void ln_bwd_kernel(const T *__restrict__ dy, const float *__restrict__ x,
@@ -192,12 +237,31 @@ int ln_backward_max_blocks() { return kLnBwdBlocks; }
 hipError_t ln_forward(int dtype, const float *x, const void *gamma, const void *beta, float eps, int rows,
                       int d, void *y, float *stats, float *xcopy, hipStream_t s) {
   dim3 grid((rows + kWaves - 1) / kWaves);
-  if (dtype == 0)
+#define IL_LN_FWD_VEC(T, J)                                                                                   \
+  hipLaunchKernelGGL((ln_fwd_vec_kernel<T, J>), grid, dim3(256), 0, s, x, (const T *)gamma, (const T *)beta, \
+                     eps, rows, (T *)y, stats, xcopy)
+  if (dtype != 0 && (d == 256 || d == 512 || d == 1024 || d == 2048)) {
+    switch (d / 256) {
+      case 1: IL_LN_FWD_VEC(bf16_t, 1); break;
+      case 2: IL_LN_FWD_VEC(bf16_t, 2); break;
+      case 4: IL_LN_FWD_VEC(bf16_t, 4); break;
+      default: IL_LN_FWD_VEC(bf16_t, 8); break;
+    }
+  } else if (dtype == 0 && (d == 256 || d == 512 || d == 1024 || d == 2048)) {
+    switch (d / 256) {
+      case 1: IL_LN_FWD_VEC(float, 1); break;
+      case 2: IL_LN_FWD_VEC(float, 2); break;
+      case 4: IL_LN_FWD_VEC(float, 4); break;
+      default: IL_LN_FWD_VEC(float, 8); break;
+    }
+  } else if (dtype == 0) {
     hipLaunchKernelGGL(ln_fwd_kernel<float>, grid, dim3(256), 0, s, x, (const float *)gamma,
                        (const float *)beta, eps, rows, d, (float *)y, stats, xcopy);
-  else
+  } else {
     hipLaunchKernelGGL(ln_fwd_kernel<bf16_t>, grid, dim3(256), 0, s, x, (const bf16_t *)gamma,
                        (const bf16_t *)beta, eps, rows, d, (bf16_t *)y, stats, xcopy);
+  }
+#undef IL_LN_FWD_VEC
   return hipGetLastError();
 }
 

@@ -57,6 +57,14 @@ def test_fp32_single_component_and_single_token():
     say("worst", compare(w, got, ref, "K1T1"))
 
 
+def test_fp32_model_width_256():
+    """d = 256 takes the 16-byte LayerNorm paths in fp32 as well."""
+    w = synth.Workload("w256", "f32", K=2, L=1, d=256, H=4, m=512, V=96, B=2, T=24, n=2)
+    say("case fp32 d=256")
+    got, ref = run_both(w, seed=6)
+    say("worst", compare(w, got, ref, "w256"))
+
+
 def test_head_chunking_does_not_change_results():
     w = TINY
     params, x0, tgt = make_inputs(w)
