@@ -99,9 +99,10 @@ struct TokTile {
 // ------------------------------------------------------------------ forward -------------
 // grid (ceil(T/128), B*H); 4 wavefronts, each owns 32 queries; key tiles of 64.
 template <int DH>
-__global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16_t *__restrict__ qkv, int T, int H,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(DH > 64 ? 1 : 2, DH > 64 ? 1 : 2))) void attn_fwd_mfma(const bf16_t *__restrict__ qkv, int T, int H,
                                                      bf16_t *__restrict__ o, float *__restrict__ lse) {
-  constexpr int BQ = 128, BKV = 64;
+  constexpr int BQ = 128, BKV = 64, NA = BKV / 32;
+  constexpr bool HOIST = DH <= 64;  // the wider head has no registers to spare for a whole tile of fragments
   constexpr int KT = BKV * DH * 2, STAGE = 2 * KT;
   typedef TokTile<BKV, DH> Tile;
   __shared__ __attribute__((aligned(16))) char smem[2 * STAGE];
@@ -146,28 +147,33 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16_t *__restrict__ 
     // every fragment of tile kt is requested before the loads of tile kt+1 are issued, so the
     // reads do not wait for data that is still on its way from memory.
     const bool live = kv0 <= qw0 + 31;  // some key of the tile is visible to some query of this wavefront
-    bf16x8 kf[2][DH / 16], vf[2][2][DH / 32];
+    bf16x8 kf[NA][DH / 16], vf[NA][2][DH / 32];
+    auto fetch = [&]() {
+      if (live) {
+#pragma unroll
+        for (int a = 0; a < NA; ++a)
+#pragma unroll
+          for (int ks = 0; ks < DH / 16; ++ks) kf[a][ks] = Tile::rowfrag(sk, 32 * a, ks, lane);
+#pragma unroll
+        for (int a = 0; a < NA; ++a)
+#pragma unroll
+          for (int bq = 0; bq < 2; ++bq)
+#pragma unroll
+            for (int dt = 0; dt < DH / 32; ++dt) vf[a][bq][dt] = Tile::trfrag(sv, 32 * a + 16 * bq, dt, lane);
+      }
+    };
+    auto prefetch = [&]() {
+      if (kt + 1 < nkv) {
+        char *nk = smem + ((kt + 1) & 1) * STAGE;
+        lk.issue(rs, nk, wave, kv0 + BKV, T);
+        lv.issue(rs, nk + KT, wave, kv0 + BKV, T);
+      }
+    };
+    if constexpr (HOIST) { fetch(); prefetch(); } else { prefetch(); fetch(); }
     if (live) {
+      floatx16 s[NA];
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int ks = 0; ks < DH / 16; ++ks) kf[a][ks] = Tile::rowfrag(sk, 32 * a, ks, lane);
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int bq = 0; bq < 2; ++bq)
-#pragma unroll
-          for (int dt = 0; dt < DH / 32; ++dt) vf[a][bq][dt] = Tile::trfrag(sv, 32 * a + 16 * bq, dt, lane);
-    }
-    if (kt + 1 < nkv) {
-      char *nk = smem + ((kt + 1) & 1) * STAGE;
-      lk.issue(rs, nk, wave, kv0 + BKV, T);
-      lv.issue(rs, nk + KT, wave, kv0 + BKV, T);
-    }
-    if (live) {
-      floatx16 s[2];
-#pragma unroll
-      for (int a = 0; a < 2; ++a) {
+      for (int a = 0; a < NA; ++a) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[a][r] = 0.f;
 #pragma unroll
@@ -177,7 +183,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16_t *__restrict__ 
       const bool diag = kv0 + BKV - 1 > qw0 || kv0 + BKV > T;
       float mx = kNegBig;
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
+      for (int a = 0; a < NA; ++a)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           float v = s[a][r] * sc;
@@ -193,7 +199,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16_t *__restrict__ 
       const float alpha = exp2f(m - mnew);
       float rs = 0.f;
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
+      for (int a = 0; a < NA; ++a)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const float p = exp2f(s[a][r] - mnew);
@@ -207,7 +213,7 @@ __global__ __launch_bounds__(256) void attn_fwd_mfma(const bf16_t *__restrict__ 
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
+      for (int a = 0; a < NA; ++a)
 #pragma unroll
         for (int bq = 0; bq < 2; ++bq) {
           Frag pf;
