@@ -113,3 +113,27 @@ def test_unsupported_combinations_are_rejected():
     assert e.value.status == b.IL_E_SHAPE
     with pytest.raises(b.InterlockError):            # N not a multiple of 8
         b.il_test_gemm(b.IL_BF16, x, x, 64, 60, 64, 64, 64, 0, 0, 0, x, ldc=64)
+
+
+# the (layout, epilogue) pairs the library instantiates: forward, data gradient, weight gradient
+_COMBOS = [(0, 1, 0), (0, 1, 1), (0, 1, 2), (0, 1, 3), (0, 0, 0), (0, 0, 4), (0, 0, 5), (1, 1, 6)]
+
+
+def test_seeded_random_shapes_every_tile_choice():
+    """A seeded sweep over sizes from a single 8-wide sliver to several tiles with ragged edges in
+    all three dimensions; tile = 0 lets the library choose, the others force each configuration."""
+    rng = np.random.default_rng(20100411)
+    dims = [8, 16, 24, 40, 64, 72, 120, 128, 136, 200, 256, 264, 328, 520]
+    for case in range(36):
+        M, N, K = (int(rng.choice(dims)) for _ in range(3))
+        akm, bkm, epi = _COMBOS[case % len(_COMBOS)]
+        tile = [0, 1, 2, 3, 4][case % 5]
+        print("case", case, M, N, K, akm, bkm, epi, "tile", tile, flush=True)
+        run_case(M, N, K, akm, bkm, epi, tile, seed=1000 + case, beta=case & 1, scale=0.5 if case & 2 else 1.0)
+
+
+def test_long_reduction_and_thin_outputs():
+    """The shapes of the head's data gradient (tiny output, very long K) and of a bias-sized sliver."""
+    run_case(64, 8, 8192, 0, 0, 5, 0, seed=77)
+    run_case(8, 64, 4104, 1, 1, 6, 0, seed=78, beta=1, scale=0.25)
+    run_case(72, 8, 520, 0, 1, 3, 0, seed=79)
