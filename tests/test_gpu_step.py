@@ -118,6 +118,25 @@ def test_bf16_reduced_small():
     say("worst", compare(w, got, ref, "small_q"))
 
 
+@pytest.mark.parametrize("T,H", [(96, 4), (160, 2), (32, 4), (224, 2)])
+def test_bf16_sequence_lengths_off_the_attention_tiles(T, H):
+    """Sequence lengths that are not multiples of the 64- / 128-row attention tiles, for both MFMA
+    head widths (d = 256: H = 4 -> 64, H = 2 -> 128); N = B*T stays a multiple of 64."""
+    w = synth.Workload("seq", "bf16", K=2, L=1, d=256, H=H, m=512, V=512, B=2, T=T, n=2)
+    say("case bf16 T =", T, "head width", 256 // H)
+    got, ref = run_both(w, seed=7)
+    say("worst", compare(w, got, ref, f"T={T} H={H}"))
+
+
+@pytest.mark.parametrize("route,n", [("mean_local_far", 3), ("far_head", 2)])
+def test_bf16_paper_routes(route, n):
+    """The paper's two routings in bf16 (stacked streams, several runs per component, scaled sums)."""
+    w = synth.Workload("routes", "bf16", K=4, L=1, d=256, H=4, m=512, V=1024, B=2, T=64, n=n)
+    say("case bf16 route", route, "n =", n)
+    got, ref = run_both(w, seed=8, route=route)
+    say("worst", compare(w, got, ref, f"{route} n={n}"))
+
+
 @pytest.mark.parametrize("n", [1, 2])
 def test_small_bf16_full_step(n):
     w = synth.WORKLOADS["small"].with_(n=n)
