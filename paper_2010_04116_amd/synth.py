@@ -131,6 +131,15 @@ def make_tokens(w: Workload, seed: int = TOKEN_SEED) -> Tuple[np.ndarray, np.nda
     return tok[:, :-1].astype(np.int32), tok[:, 1:].astype(np.int32)
 
 
+def make_embeddings(w: Workload, seed: int = PARAM_SEED):
+    """The seeded token and position tables (wte [V, d], wpe [T, d], N(0, 0.02^2), float32 values
+    representable in the storage dtype) that make_x0 draws internally."""
+    g = _rng(seed, 2000)
+    wte = g.standard_normal((w.V, w.d), dtype=np.float32) * np.float32(0.02)
+    wpe = g.standard_normal((w.T, w.d), dtype=np.float32) * np.float32(0.02)
+    return _store(w, wte), _store(w, wpe)
+
+
 def make_x0(w: Workload, inputs: np.ndarray, seed: int = PARAM_SEED) -> np.ndarray:
     """x_0[b,t] = wte[token] + wpe[t], float32 [B*T, d], values representable in
     the storage dtype.  The embedding tables are drawn here and not returned:
