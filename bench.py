@@ -168,6 +168,7 @@ def measure(w, steps, warmup):
         "losses": [float(x) for x in losses],
     }
     res["optimizer"] = optimizer_line(w)
+    res["embedding"] = embedding_line(w)
     return res, params, x0, tgt
 
 
@@ -202,6 +203,42 @@ def optimizer_line(w, reps=10):
     gbs = count * per / (ms * 1e-3) / 1e9
     return {"kernel": "adam_step_kernel", "parameters": count, "ms": ms, "bound": "hbm", "achieved": gbs,
             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "bytes_per_parameter": per}
+
+
+def embedding_line(w, reps=10):
+    """Input embedding (App. B: module 1 holds the embedding matrix) and its gradient at this workload's
+    shape, timed on their own; HBM-bound kernels, not part of `value`."""
+    import torch
+    from paper_2010_04116_amd import binding, synth
+    dev = "cuda:0"
+    tt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    eb = 2 if w.dtype == "bf16" else 4
+    wte, wpe = synth.make_embeddings(w)
+    inp, _ = synth.make_tokens(w)
+    d_wte, d_wpe = torch.from_numpy(wte).to(tt).to(dev), torch.from_numpy(wpe).to(tt).to(dev)
+    tok = torch.from_numpy(inp.reshape(-1).astype(np.int32)).to(dev)
+    x0 = torch.empty(w.N, w.d, device=dev)
+    dx0 = torch.randn(w.N, w.d, device=dev)
+    dwte, dwpe = torch.empty(w.V, w.d, device=dev), torch.empty(w.T, w.d, device=dev)
+    st = torch.cuda.current_stream()
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for _ in range(reps):
+            fn()
+        e1.record(st)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+    f_ms = timed(lambda: binding.il_embed_forward(w.dtype, d_wte, d_wpe, tok, w.B, w.T, w.d, w.V, x0,
+                                                  stream=st.cuda_stream))
+    b_ms = timed(lambda: binding.il_embed_backward(dx0, tok, w.B, w.T, w.d, w.V, dwte, dwpe, stream=st.cuda_stream))
+    f_bytes = w.N * w.d * (eb + 4) + w.T * w.d * eb            # gathered rows + positions read, x0 written
+    b_bytes = 2 * w.N * w.d * 4 + (w.V + w.T) * w.d * 4         # dx0 read by both kernels, both tables written
+    return {"forward_ms": f_ms, "forward_gbs": f_bytes / (f_ms * 1e-3) / 1e9,
+            "backward_ms": b_ms, "backward_gbs": b_bytes / (b_ms * 1e-3) / 1e9, "bound": "hbm",
+            "peak": PEAK_HBM_GBS, "unit": "GB/s"}
 
 
 def config_of(w):

@@ -196,6 +196,31 @@ int il_test_gemm(int32_t dtype, const void *A, const void *B, int32_t M, int32_t
                  const void *bias, const float *res, const void *aux, int32_t aux_wrap, float scale,
                  int32_t beta, int32_t tile, void *stream);
 
+/* ---- input embedding of the first module (App. B: the embedding matrix in front of the blocks) ---- */
+
+/*
+ * x0[b*seq + t, :] = wte[tokens[b*seq + t], :] + wpe[t, :], fp32 [batch*seq, d_model]: the x_in of
+ * il_stage_forward(1).  wte [vocab, d_model] and wpe [seq, d_model] are row-major in `dtype`
+ * (il_dtype); tokens is int32 [batch*seq]; all device pointers owned by the caller; enqueued on
+ * `stream`.  A token outside [0, vocab) embeds as the zero vector (nothing out of bounds is read).
+ * IL_E_ARG: NULL pointer, non-positive size, unknown dtype; IL_E_SHAPE: batch*seq or vocab above
+ * 2^24, or x0 not 16-byte aligned when d_model is a multiple of 4.
+ */
+int il_embed_forward(int32_t dtype, const void *wte, const void *wpe, const int32_t *tokens, int32_t batch,
+                     int32_t seq, int32_t d_model, int32_t vocab, float *x0, void *stream);
+
+/*
+ * Gradient of the embedding, from dx0 fp32 [batch*seq, d_model] (the dx0_out of
+ * il_stage_backward_nwise(1)):
+ *   dwte[v, :] = sum over the positions i with tokens[i] == v of dx0[i, :]   (zero for unused rows),
+ *   dwpe[t, :] = sum_b dx0[b*seq + t, :],
+ * both fp32, every element written exactly once per call (no zeroing needed), no atomics, fixed
+ * summation order (ascending position), so the result is bit-reproducible.  Tokens outside
+ * [0, vocab) receive no gradient.  Same error codes as il_embed_forward.
+ */
+int il_embed_backward(const float *dx0, const int32_t *tokens, int32_t batch, int32_t seq, int32_t d_model,
+                      int32_t vocab, float *dwte, float *dwpe, void *stream);
+
 /* ---- optimiser step (App. B, training configuration of the Transformer runs) ------ */
 
 /*

@@ -23,7 +23,7 @@ IL_F32, IL_BF16 = 0, 1
 ROUTES = {"window_sum": 0, "far_head": 1, "mean_local_far": 2}
 SYMBOLS = ("il_init", "il_stage_forward", "il_head_xent", "il_stage_backward_nwise", "il_free",
            "il_routing_plan", "il_profile_read", "il_status_string", "il_test_gemm", "il_lr_schedule",
-           "il_adam_step")
+           "il_adam_step", "il_embed_forward", "il_embed_backward")
 
 
 class il_config(C.Structure):
@@ -67,6 +67,8 @@ def load():
     lib.il_lr_schedule.restype = C.c_double
     lib.il_adam_step.argtypes = [i32, vp, vp, vp, vp, vp, C.c_size_t, C.c_int64, C.c_float, C.c_float, C.c_float,
                                  C.c_float, vp]
+    lib.il_embed_forward.argtypes = [i32, vp, vp, vp, i32, i32, i32, i32, vp, vp]
+    lib.il_embed_backward.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp]
     lib.il_status_string.argtypes = [C.c_int]
     lib.il_status_string.restype = C.c_char_p
     for name in SYMBOLS:
@@ -171,6 +173,21 @@ def il_profile_read(ctx) -> Dict[str, dict]:
         raise InterlockError(cnt, "il_profile_read")
     return {names[i].decode(): dict(launches=n[i], ms=ms[i], flops=fl[i], bytes=by[i], kernel_ms=kms[i])
             for i in range(cnt)}
+
+
+def _ptr(x):
+    return None if x is None else (x.data_ptr() if hasattr(x, "data_ptr") else x)
+
+
+def il_embed_forward(dtype, wte, wpe, tokens, batch: int, seq: int, d_model: int, vocab: int, x0, stream=None):
+    dt = {"f32": IL_F32, "bf16": IL_BF16}[dtype] if isinstance(dtype, str) else dtype
+    _check(load().il_embed_forward(dt, _ptr(wte), _ptr(wpe), _ptr(tokens), batch, seq, d_model, vocab, _ptr(x0),
+                                   stream), "il_embed_forward")
+
+
+def il_embed_backward(dx0, tokens, batch: int, seq: int, d_model: int, vocab: int, dwte, dwpe, stream=None):
+    _check(load().il_embed_backward(_ptr(dx0), _ptr(tokens), batch, seq, d_model, vocab, _ptr(dwte), _ptr(dwpe),
+                                    stream), "il_embed_backward")
 
 
 def il_lr_schedule(step: int, d_model: int, warmup_steps: int = 4000) -> float:
