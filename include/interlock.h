@@ -109,7 +109,7 @@ typedef struct il_config {
  * Size query: call with cfg->workspace == NULL; the three *_bytes fields are filled
  * with the required sizes, *out is left NULL and IL_E_WORKSPACE is returned.
  * Limits (IL_E_SHAPE otherwise): d_model a multiple of n_heads with head width
- * d_model / n_heads in {16, 32, 64, 128}; d_model <= 2048; batch*seq <= 2^24; vocab <= 2^24;
+ * d_model / n_heads in {16, 32, 64, 128}, or 256 in bf16 mode; d_model <= 2048; batch*seq <= 2^24; vocab <= 2^24;
  * in bf16 mode d_model, d_mlp and vocab multiples of 8, batch*seq and head_chunk multiples of
  * 64.  At most 16 merged gradient streams may be live at one component.
  * The workspace must be 256-byte aligned.

@@ -147,8 +147,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(DH > 64 ? 1
     // every fragment of tile kt is requested before the loads of tile kt+1 are issued, so the
     // reads do not wait for data that is still on its way from memory.
     const bool live = kv0 <= qw0 + 31;  // some key of the tile is visible to some query of this wavefront
-    bf16x8 kf[NA][DH / 16], vf[NA][2][DH / 32];
+    bf16x8 kf[HOIST ? NA : 1][HOIST ? DH / 16 : 1], vf[HOIST ? NA : 1][2][HOIST ? DH / 32 : 1];
     auto fetch = [&]() {
+      if constexpr (!HOIST) return;  // fragments are read where they are used
       if (live) {
 #pragma unroll
         for (int a = 0; a < NA; ++a)
@@ -169,7 +170,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(DH > 64 ? 1
         lv.issue(rs, nk + KT, wave, kv0 + BKV, T);
       }
     };
-    if constexpr (HOIST) { fetch(); prefetch(); } else { prefetch(); fetch(); }
+    if constexpr (HOIST) { fetch(); prefetch(); } else { prefetch(); }
     if (live) {
       floatx16 s[NA];
 #pragma unroll
@@ -178,7 +179,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(DH > 64 ? 1
         for (int r = 0; r < 16; ++r) s[a][r] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < DH / 16; ++ks)
-          s[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[a][ks], qf[ks].v, s[a], 0, 0, 0);
+          s[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(HOIST ? kf[HOIST ? a : 0][HOIST ? ks : 0] : Tile::rowfrag(sk, 32 * a, ks, lane),
+                                                         qf[ks].v, s[a], 0, 0, 0);
       }
       const bool diag = kv0 + BKV - 1 > qw0 || kv0 + BKV > T;
       float mx = kNegBig;
@@ -221,7 +223,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(DH > 64 ? 1
           for (int e = 0; e < 4; ++e) pf.u[e] = pack2(s[a][8 * bq + 2 * e], s[a][8 * bq + 2 * e + 1]);
 #pragma unroll
           for (int dt = 0; dt < DH / 32; ++dt)
-            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[a][bq][dt], pf.v, oacc[dt], 0, 0, 0);
+            oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                HOIST ? vf[HOIST ? a : 0][bq][HOIST ? dt : 0] : Tile::trfrag(sv, 32 * a + 16 * bq, dt, lane), pf.v, oacc[dt], 0,
+                0, 0);
         }
     }
   }
@@ -518,6 +522,8 @@ hipError_t attention_forward_mfma(const void *qkv, int B, int T, int H, int dh, 
     hipLaunchKernelGGL(attn_fwd_mfma<64>, grid, dim3(256), 0, s, (const bf16_t *)qkv, T, H, (bf16_t *)o, lse);
   else if (dh == 128)
     hipLaunchKernelGGL(attn_fwd_mfma<128>, grid, dim3(256), 0, s, (const bf16_t *)qkv, T, H, (bf16_t *)o, lse);
+  else if (dh == 256)
+    hipLaunchKernelGGL(attn_fwd_mfma<256>, grid, dim3(256), 0, s, (const bf16_t *)qkv, T, H, (bf16_t *)o, lse);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();
@@ -535,6 +541,11 @@ hipError_t attention_backward_mfma(const void *qkv, const void *o, const void *d
     hipLaunchKernelGGL(attn_bwd_dq_mfma<128>, grid, dim3(256), 0, s, (const bf16_t *)qkv, (const bf16_t *)o,
                        (const bf16_t *)d_o, lse, B, T, H, (bf16_t *)dqkv, dsum);
     hipLaunchKernelGGL(attn_bwd_dkv_mfma<128>, grid, dim3(256), 0, s, (const bf16_t *)qkv, (const bf16_t *)d_o, lse,
+                       dsum, B, T, H, (bf16_t *)dqkv);
+  } else if (dh == 256) {
+    hipLaunchKernelGGL(attn_bwd_dq_mfma<256>, grid, dim3(256), 0, s, (const bf16_t *)qkv, (const bf16_t *)o,
+                       (const bf16_t *)d_o, lse, B, T, H, (bf16_t *)dqkv, dsum);
+    hipLaunchKernelGGL(attn_bwd_dkv_mfma<256>, grid, dim3(256), 0, s, (const bf16_t *)qkv, (const bf16_t *)d_o, lse,
                        dsum, B, T, H, (bf16_t *)dqkv);
   } else {
     return hipErrorInvalidValue;

@@ -180,12 +180,12 @@ hipError_t attention_backward_mfma(const void *qkv, const void *o, const void *d
 // everything else (fp32; bf16 with head width 16 or 32) on the kernels above.
 hipError_t attention_forward(int dtype, const void *qkv, int B, int T, int H, int dh, void *o, float *lse,
                              hipStream_t s) {
-  if (dtype == 1 && (dh == 64 || dh == 128)) return attention_forward_mfma(qkv, B, T, H, dh, o, lse, s);
+  if (dtype == 1 && (dh == 64 || dh == 128 || dh == 256)) return attention_forward_mfma(qkv, B, T, H, dh, o, lse, s);
   return attention_forward_simt(dtype, qkv, B, T, H, dh, o, lse, s);
 }
 hipError_t attention_backward(int dtype, const void *qkv, const void *o, const void *d_o, const float *lse,
                               int ns, int B, int T, int H, int dh, void *dqkv, float *dsum, hipStream_t s) {
-  if (dtype == 1 && (dh == 64 || dh == 128))
+  if (dtype == 1 && (dh == 64 || dh == 128 || dh == 256))
     return attention_backward_mfma(qkv, o, d_o, lse, ns, B, T, H, dh, dqkv, dsum, s);
   return attention_backward_simt(dtype, qkv, o, d_o, lse, ns, B, T, H, dh, dqkv, dsum, s);
 }

@@ -579,7 +579,7 @@ int validate(const il_config *cfg) {
   if (cfg->head_chunk < 0) return IL_E_ARG;
   if (cfg->d_model % cfg->n_heads) return IL_E_SHAPE;
   const int dh = cfg->d_model / cfg->n_heads;
-  if (dh != 16 && dh != 32 && dh != 64 && dh != 128) return IL_E_SHAPE;
+  if (dh != 16 && dh != 32 && dh != 64 && dh != 128 && !(dh == 256 && cfg->dtype == IL_BF16)) return IL_E_SHAPE;
   if (cfg->d_model > 2048) return IL_E_SHAPE;
   const long long N = (long long)cfg->batch * cfg->seq;
   if (N > (1 << 24) || (long long)cfg->vocab > (1 << 24)) return IL_E_SHAPE;

@@ -118,10 +118,10 @@ def test_bf16_reduced_small():
     say("worst", compare(w, got, ref, "small_q"))
 
 
-@pytest.mark.parametrize("T,H", [(96, 4), (160, 2), (32, 4), (224, 2)])
+@pytest.mark.parametrize("T,H", [(96, 4), (160, 2), (32, 4), (224, 2), (128, 1), (96, 1)])
 def test_bf16_sequence_lengths_off_the_attention_tiles(T, H):
     """Sequence lengths that are not multiples of the 64- / 128-row attention tiles, for both MFMA
-    head widths (d = 256: H = 4 -> 64, H = 2 -> 128); N = B*T stays a multiple of 64."""
+    head widths (d = 256: H = 4 -> 64, H = 2 -> 128, H = 1 -> 256, the paper's); N = B*T stays a multiple of 64."""
     w = synth.Workload("seq", "bf16", K=2, L=1, d=256, H=H, m=512, V=512, B=2, T=T, n=2)
     say("case bf16 T =", T, "head width", 256 // H)
     got, ref = run_both(w, seed=7)
@@ -291,3 +291,8 @@ def test_many_head_full_size_sampled():
 
 def test_large_full_size_sampled():
     _sampled_full_size("large", 13)
+
+
+def test_paper_shape_full_size_sampled():
+    """The paper's module shape (head width 256, sequences of 128, 6 blocks per module)."""
+    _sampled_full_size("paper", 14)
