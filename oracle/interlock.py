@@ -181,6 +181,17 @@ def head_xent(x, w_head, targets):
     return loss, dz @ w_head.T, x.T @ dz
 
 
+def aux_head(x, head_blocks, w_head, targets, B, T, H, eps):
+    """Auxiliary network of one module and its local loss (Sec. 3, the local-loss equation).  The
+    paper's Transformer runs use Transformer blocks followed by the output embedding matrix (App. B,
+    module table); with no blocks this is the bare linear head.  Returns
+    (loss, dL/dx, dL/dW_head, [dL/d(block parameters)])."""
+    y, caches = component_forward(x, head_blocks, B, T, H, eps)
+    loss, dy, dw = head_xent(y, w_head, targets)
+    dx, gblocks = component_backward(dy, head_blocks, caches)
+    return loss, dx, dw, gblocks
+
+
 # --------------------------------------------------------------------------
 # routing
 # --------------------------------------------------------------------------
@@ -248,18 +259,27 @@ def _to_f64(params):
     return comps, heads
 
 
+def _head_blocks_f64(params):
+    hb = params.get("head_blocks") or [[] for _ in params["heads"]]
+    return [[{k: np.asarray(v, dtype=F64) for k, v in p.items()} for p in blocks] for blocks in hb]
+
+
 def forward_all(params, x0, targets, B, T, H, eps=1e-5):
     """Forward through all K components and heads.  Returns per-component
-    caches, activations x_1..x_K, the K losses, dL_j/dx_j and dL_j/dW_head,j."""
+    caches, activations x_1..x_K, the K losses, dL_j/dx_j, dL_j/dW_head,j and the
+    gradients of the heads' own blocks."""
     comps, heads = _to_f64(params)
+    hblocks = _head_blocks_f64(params)
     x = np.asarray(x0, dtype=F64)
     tg = np.asarray(targets).reshape(-1)
     xs, caches, losses, dxs, dheads = [], [], [], [], []
-    for blocks, wh in zip(comps, heads):
+    dhblocks = []                         # gradients of the heads' own blocks (L_k only, weight 1)
+    for blocks, wh, hb in zip(comps, heads, hblocks):
         x, c = component_forward(x, blocks, B, T, H, eps)
-        loss, dx, dw = head_xent(x, wh, tg)
+        loss, dx, dw, ghb = aux_head(x, hb, wh, tg, B, T, H, eps)
         xs.append(x); caches.append(c); losses.append(loss); dxs.append(dx); dheads.append(dw)
-    return comps, heads, xs, caches, np.array(losses), dxs, dheads
+        dhblocks.append(ghb)
+    return comps, heads, xs, caches, np.array(losses), dxs, dheads, dhblocks
 
 
 def nwise_definition(params, x0, targets, B, T, H, n, route="window_sum", eps=1e-5,
@@ -267,7 +287,7 @@ def nwise_definition(params, x0, targets, B, T, H, n, route="window_sum", eps=1e
     """Definition path: for every head j run an ordinary, untruncated backward of
     L_j alone down to component 1, keep dL_j/dtheta_k for all k <= j, then combine
     with the routing weights.  Returns dict(losses, comp_grads, head_grads, dx0)."""
-    comps, heads, xs, caches, losses, dxs, dheads = forward_all(params, x0, targets, B, T, H, eps)
+    comps, heads, xs, caches, losses, dxs, dheads, dhblocks = forward_all(params, x0, targets, B, T, H, eps)
     K = len(comps)
     w = routing_weights(K, n, route)
     acc = [_zeros_like_grads(b) for b in comps]
@@ -280,7 +300,8 @@ def nwise_definition(params, x0, targets, B, T, H, n, route="window_sum", eps=1e
             table[(k, j)] = gr
             _axpy(acc[k - 1], w[k - 1, j - 1], gr)
         dx0 += w[0, j - 1] * g
-    out = dict(losses=losses, comp_grads=acc, head_grads=dheads, dx0=dx0)
+    out = dict(losses=losses, comp_grads=acc, head_grads=dheads, dx0=dx0,
+               head_block_grads=dhblocks)
     if return_table:
         out["table"] = table
     return out
@@ -291,7 +312,7 @@ def nwise_streams(params, x0, targets, B, T, H, n, route="window_sum", eps=1e-5)
     separately through component k's backward, credit its parameter gradient with
     the routing weight, and drop the stream once it has passed its lowest
     crediting component (stop-gradient at the window edge)."""
-    comps, heads, xs, caches, losses, dxs, dheads = forward_all(params, x0, targets, B, T, H, eps)
+    comps, heads, xs, caches, losses, dxs, dheads, dhblocks = forward_all(params, x0, targets, B, T, H, eps)
     K = len(comps)
     w = routing_weights(K, n, route)
     plan = stream_plan(K, n, route)
@@ -312,4 +333,4 @@ def nwise_streams(params, x0, targets, B, T, H, n, route="window_sum", eps=1e-5)
     for j, g in live.items():
         dx0 += w[0, j - 1] * g
     return dict(losses=losses, comp_grads=acc, head_grads=dheads, dx0=dx0,
-                backward_passes=passes[::-1])
+                head_block_grads=dhblocks, backward_passes=passes[::-1])

@@ -33,6 +33,7 @@ class Workload:
     B: int          # batch (sequences)
     T: int          # sequence length
     n: int          # n-wise window
+    Lh: int = 0     # Transformer blocks inside each auxiliary head, in front of its d -> V map
 
     @property
     def N(self) -> int:
@@ -120,11 +121,14 @@ def make_head_params(w: Workload, k: int, seed: int = PARAM_SEED) -> np.ndarray:
 
 def make_params(w: Workload, seed: int = PARAM_SEED, random_bias: bool = False,
                 random_ln: bool = False) -> dict:
-    """{'components': [[block dict]*L]*K, 'heads': [w_head]*K}."""
+    """{'components': [[block dict]*L]*K, 'heads': [w_head]*K, 'head_blocks': [[block dict]*Lh]*K}."""
     comps = [[make_block_params(w, k, l, seed, random_bias, random_ln)
               for l in range(1, w.L + 1)] for k in range(1, w.K + 1)]
     heads = [make_head_params(w, k, seed) for k in range(1, w.K + 1)]
-    return {"components": comps, "heads": heads}
+    # the blocks of head k are drawn like those of a component numbered 1000 + k
+    hblocks = [[make_block_params(w, 1000 + k, l, seed, random_bias, random_ln)
+                for l in range(1, w.Lh + 1)] for k in range(1, w.K + 1)]
+    return {"components": comps, "heads": heads, "head_blocks": hblocks}
 
 
 def make_tokens(w: Workload, seed: int = TOKEN_SEED) -> Tuple[np.ndarray, np.ndarray]:
