@@ -50,6 +50,7 @@ def minimal_flops(w):
         tot += w.L * (G + At)                                   # forward
         tot += w.L * ((live[k] + 1) * G + 2.5 * live[k] * At)   # dgrad per stream + one wgrad
         tot += 3 * 2.0 * N * d * w.V                            # head fwd + dx + dW
+        tot += w.Lh * ((G + At) + (2 * G + 2.5 * At))           # the head's own blocks: forward, one stream back
     return tot
 
 
@@ -245,6 +246,7 @@ def config_of(w):
     from paper_2010_04116_amd import synth
     return {"workload": f"{w.name}_{w.dtype}_n{w.n}", "K": w.K, "blocks_per_component": w.L,
             "d_model": w.d, "n_heads": w.H, "d_mlp": w.m, "vocab": w.V, "batch": w.B, "seq": w.T,
+            "head_blocks": w.Lh,
             "n": w.n, "route": "window_sum", "param_seed": synth.PARAM_SEED, "token_seed": synth.TOKEN_SEED}
 
 

@@ -70,7 +70,8 @@ typedef enum { IL_ROUTE_WINDOW_SUM = 0, IL_ROUTE_FAR_HEAD = 1, IL_ROUTE_MEAN_LOC
  * Problem statement.  Each component is `blocks_per_component` pre-LN Transformer
  * blocks:  a = x + O(Attn(QKV(LN1 x))),  x' = a + FC2(GELU(FC1(LN2 a)))  with causal
  * attention, tanh-GELU, biased-variance LayerNorm with ln_eps inside the root.
- * Head k is a bias-free linear map d_model -> vocab; loss k is the mean over the
+ * Head k is `head_blocks` further blocks of the same form (its own parameters, trained by L_k
+ * alone) followed by a bias-free linear map d_model -> vocab; loss k is the mean over the
  * batch*seq positions of the natural-log cross-entropy against `targets`.
  *
  * Flat parameter layout (element type = dtype; every matrix row-major, y = x W + b,
@@ -78,7 +79,7 @@ typedef enum { IL_ROUTE_WINDOW_SUM = 0, IL_ROUTE_FAR_HEAD = 1, IL_ROUTE_MEAN_LOC
  *   for component 1..K, for block 1..L:
  *     ln1_g[d] ln1_b[d] w_qkv[d,3d] b_qkv[3d] w_o[d,d] b_o[d]
  *     ln2_g[d] ln2_b[d] w_fc1[d,m] b_fc1[m] w_fc2[m,d] b_fc2[d]
- *   then heads 1..K: w_head[d,V]
+ *   then heads 1..K: head_blocks blocks (the same twelve tensors each), w_head[d,V]
  * w_qkv's columns are Q | K | V, each split into n_heads groups of d/n_heads columns.
  * `grads` has the same element order in fp32.  Every gradient element is overwritten
  * exactly once per step (no zeroing needed, nothing accumulates across steps).
@@ -95,6 +96,10 @@ typedef struct il_config {
   int32_t head_chunk;           /* token rows per head chunk (0 = library default);
                                    only a [head_chunk, vocab] logits tile ever exists */
   int32_t profile;              /* nonzero: record per-kernel-class HIP event times   */
+  int32_t head_blocks;          /* Transformer blocks inside every auxiliary head, in front
+                                   of its d_model -> vocab map (0 = the bare linear head;
+                                   the paper's Transformer runs use 2, App. B)          */
+  int32_t reserved;             /* must be 0                                          */
   void *params;                 /* device, flat layout above                         */
   size_t params_bytes;
   void *grads;                  /* device, fp32, same order                          */
@@ -129,7 +134,8 @@ int il_stage_forward(il_ctx *ctx, int32_t k, const float *x_in, float *x_out);
  * Auxiliary head k and its local loss L_k = xent(h_k(x_k), y) (Sec. 3, the equation
  * defining the local loss).  x_k: device fp32 [N, d_model]; targets: device int32 [N],
  * each in [0, vocab); loss_out: device fp32 scalar (mean over N, natural log).
- * Writes dL_k/dW_head,k into grads and keeps dL_k/dx_k in the workspace as the
+ * Writes dL_k/dW_head,k (and the gradients of the head's own blocks) into grads and keeps
+ * dL_k/dx_k - propagated back through those blocks - in the workspace as the
  * gradient stream of head k (age 0) for il_stage_backward_nwise.  Logits and
  * probabilities exist only one [head_chunk, vocab] tile at a time.
  * Order: after il_stage_forward(k) of the same step.

@@ -31,7 +31,8 @@ class il_config(C.Structure):
                 ("n_heads", C.c_int32), ("d_mlp", C.c_int32), ("vocab", C.c_int32),
                 ("batch", C.c_int32), ("seq", C.c_int32), ("n", C.c_int32), ("dtype", C.c_int32),
                 ("route", C.c_int32), ("ln_eps", C.c_float), ("head_chunk", C.c_int32),
-                ("profile", C.c_int32), ("params", C.c_void_p), ("params_bytes", C.c_size_t),
+                ("profile", C.c_int32), ("head_blocks", C.c_int32), ("reserved", C.c_int32),
+                ("params", C.c_void_p), ("params_bytes", C.c_size_t),
                 ("grads", C.c_void_p), ("grads_bytes", C.c_size_t), ("workspace", C.c_void_p),
                 ("workspace_bytes", C.c_size_t), ("stream", C.c_void_p)]
 
@@ -102,6 +103,7 @@ def make_config(w: synth.Workload, route: str = "window_sum", head_chunk: int = 
     cfg.ln_eps = ln_eps
     cfg.head_chunk = head_chunk
     cfg.profile = int(profile)
+    cfg.head_blocks = w.Lh
     return cfg
 
 
@@ -210,7 +212,7 @@ def il_adam_step(dtype, params, master, grads, m, v, count: int, step: int, lr: 
 
 def param_count(w: synth.Workload) -> int:
     per_block = sum(int(np.prod(s)) for s in synth.block_shapes(w).values())
-    return w.K * w.L * per_block + w.K * w.d * w.V
+    return w.K * (w.L + w.Lh) * per_block + w.K * w.d * w.V
 
 
 def pack_params(w: synth.Workload, params: dict) -> np.ndarray:
@@ -223,7 +225,14 @@ def pack_params(w: synth.Workload, params: dict) -> np.ndarray:
                 a = b[name].ravel()
                 out[o:o + a.size] = a
                 o += a.size
-    for h in params["heads"]:
+    hblocks = params.get("head_blocks") or [[] for _ in params["heads"]]
+    for h, hb in zip(params["heads"], hblocks):
+        assert len(hb) == w.Lh
+        for b in hb:                                   # the head's own blocks come before its matrix
+            for name in synth.BLOCK_TENSORS:
+                a = b[name].ravel()
+                out[o:o + a.size] = a
+                o += a.size
         out[o:o + h.size] = h.ravel()
         o += h.size
     assert o == out.size
@@ -244,11 +253,20 @@ def unpack_grads(w: synth.Workload, flat: np.ndarray) -> dict:
                 o += n
             blocks.append(b)
         comps.append(blocks)
-    heads = []
+    heads, hblocks = [], []
     for _ in range(w.K):
+        blocks = []
+        for _ in range(w.Lh):
+            b = {}
+            for name in synth.BLOCK_TENSORS:
+                n = int(np.prod(shapes[name]))
+                b[name] = flat[o:o + n].reshape(shapes[name])
+                o += n
+            blocks.append(b)
+        hblocks.append(blocks)
         heads.append(flat[o:o + w.d * w.V].reshape(w.d, w.V))
         o += w.d * w.V
-    return {"components": comps, "heads": heads}
+    return {"components": comps, "heads": heads, "head_blocks": hblocks}
 
 
 class Step:
@@ -299,7 +317,7 @@ class Step:
         self.stream.synchronize()
         g = unpack_grads(self.w, self.grads.cpu().numpy())
         return dict(losses=self.losses.cpu().numpy().astype(np.float64), comp_grads=g["components"],
-                    head_grads=g["heads"], dx0=self.dx0.cpu().numpy(),
+                    head_grads=g["heads"], head_block_grads=g["head_blocks"], dx0=self.dx0.cpu().numpy(),
                     x=[t.cpu().numpy() for t in self.x])
 
     def close(self):

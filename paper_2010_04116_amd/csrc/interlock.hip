@@ -168,11 +168,15 @@ struct ProfRec { int cls; bool kernel; hipEvent_t e0, e1; KernelTimer kt; };
 struct il_ctx {
   il_config cfg;
   Plan plan;
-  int N, d, m, V, H, dh, L, K, eb;
+  int N, d, m, V, H, dh, L, K, eb, Lh;
   hipStream_t stream;
   std::vector<BlockOff> boff;      // K*L
   std::vector<size_t> hoff;        // K
   std::vector<BlockSave> save;     // K*L
+  std::vector<BlockOff> hboff;     // K*Lh: the heads' own blocks
+  std::vector<BlockSave> hsave;    // K*Lh
+  float *hy = nullptr;             // output of a head's last block, fp32 [N,d]
+  bool tail_inline = false;        // block_backward is running on the side stream already (inside a head)
   float *G; char *Gb;              // stream slots [nslots][N,d]
   char *DU, *DH, *DQKV, *YS[4]; float *dsum, *partials[6], *skws; size_t skws_floats; ColsumJobs jobs;
   // The end of a block's backward (final column sums, the four weight gradients) runs on the side
@@ -217,8 +221,17 @@ size_t layout_params(il_ctx *c) {
     b.w_o = o; o += d * d; b.b_o = o; o += d; b.ln2_g = o; o += d; b.ln2_b = o; o += d;
     b.w_fc1 = o; o += d * m; b.b_fc1 = o; o += m; b.w_fc2 = o; o += m * d; b.b_fc2 = o; o += d;
   }
+  auto lay = [&](BlockOff &b) {
+    b.ln1_g = o; o += d; b.ln1_b = o; o += d; b.w_qkv = o; o += 3 * d * d; b.b_qkv = o; o += 3 * d;
+    b.w_o = o; o += d * d; b.b_o = o; o += d; b.ln2_g = o; o += d; b.ln2_b = o; o += d;
+    b.w_fc1 = o; o += d * m; b.b_fc1 = o; o += m; b.w_fc2 = o; o += m * d; b.b_fc2 = o; o += d;
+  };
   c->hoff.resize(c->K);
-  for (auto &h : c->hoff) { h = o; o += d * (size_t)c->V; }
+  c->hboff.resize((size_t)c->K * c->Lh);
+  for (int k = 0; k < c->K; ++k) {
+    for (int l = 0; l < c->Lh; ++l) lay(c->hboff[(size_t)k * c->Lh + l]);
+    c->hoff[k] = o; o += d * (size_t)c->V;
+  }
   return o;
 }
 
@@ -233,7 +246,17 @@ size_t layout_workspace(il_ctx *c, void *base) {
     s.a = (float *)cv.take(N * d * 4); s.st2 = (float *)cv.take(N * 2 * 4);
     s.h2 = (char *)cv.take(N * d * eb); s.u = (char *)cv.take(N * m * eb); s.gl = (char *)cv.take(N * m * eb);
   }
-  const size_t ns = c->plan.nslots, S = (size_t)c->plan.maxcnt * N;
+  c->hsave.resize((size_t)c->K * c->Lh);
+  for (auto &s : c->hsave) {
+    s.xs = (float *)cv.take(N * d * 4); s.st1 = (float *)cv.take(N * 2 * 4);
+    s.h1 = (char *)cv.take(N * d * eb); s.qkv = (char *)cv.take(N * 3 * d * eb);
+    s.lse = (float *)cv.take(N * H * 4); s.o = (char *)cv.take(N * d * eb);
+    s.a = (float *)cv.take(N * d * 4); s.st2 = (float *)cv.take(N * 2 * 4);
+    s.h2 = (char *)cv.take(N * d * eb); s.u = (char *)cv.take(N * m * eb); s.gl = (char *)cv.take(N * m * eb);
+  }
+  if (c->Lh) c->hy = (float *)cv.take(N * d * 4);
+  // (one more stream slot carries a head's gradient through its own blocks)
+  const size_t ns = c->plan.nslots + (c->Lh ? 1 : 0), S = (size_t)std::max(c->plan.maxcnt, 1) * N;
   c->G = (float *)cv.take(ns * N * d * 4);
   c->Gb = (c->eb == 4) ? (char *)c->G : (char *)cv.take(ns * N * d * eb);
   c->DU = (char *)cv.take(S * m * eb);
@@ -400,7 +423,7 @@ int linear_wgrad(il_ctx *c, const Run &cp, const void *x, const void *dy, int Ki
   if (cp.nweighted == 0) return IL_OK;  // pass-through streams only: nothing is credited
   // (with the block tail on the side stream every operand is materialised: the scratch it would
   // be read from is rewritten by the next block meanwhile)
-  const bool in_place = cp.nweighted == 1 && cp.wscale == 1.f && !keep && c->cfg.profile;
+  const bool in_place = cp.nweighted == 1 && cp.wscale == 1.f && !keep && (c->cfg.profile || c->tail_inline);
   const char *dys = in_place ? (const char *)dy + (size_t)cp.first_weighted * c->N * Nout * c->eb : c->YS[slot];
   {
     // queued: two of a block's four reductions are ready at the same point of the backward and
@@ -515,7 +538,7 @@ int block_backward(il_ctx *c, const Run &cp, const BlockOff &b, const BlockSave 
   c->jobs.count = 0;
   c->pending.count = 0;
   c->pending_bytes = 0;
-  const bool async_tail = !c->cfg.profile;
+  const bool async_tail = !c->cfg.profile && !c->tail_inline;
   const int par = c->bparity;
   if (async_tail) {
     if ((rc = ensure_side(c))) return rc;
@@ -576,7 +599,7 @@ int validate(const il_config *cfg) {
   if (cfg->dtype != IL_F32 && cfg->dtype != IL_BF16) return IL_E_ARG;
   if (cfg->route < 0 || cfg->route > IL_ROUTE_MEAN_LOCAL_FAR) return IL_E_ARG;
   if (!(cfg->ln_eps > 0.f)) return IL_E_ARG;
-  if (cfg->head_chunk < 0) return IL_E_ARG;
+  if (cfg->head_chunk < 0 || cfg->head_blocks < 0 || cfg->head_blocks > 64 || cfg->reserved != 0) return IL_E_ARG;
   if (cfg->d_model % cfg->n_heads) return IL_E_SHAPE;
   const int dh = cfg->d_model / cfg->n_heads;
   if (dh != 16 && dh != 32 && dh != 64 && dh != 128 && !(dh == 256 && cfg->dtype == IL_BF16)) return IL_E_SHAPE;
@@ -628,6 +651,7 @@ int il_init(il_config *cfg, il_ctx **out) {
   c->K = cfg->K; c->L = cfg->blocks_per_component; c->d = cfg->d_model; c->m = cfg->d_mlp; c->V = cfg->vocab;
   c->H = cfg->n_heads; c->dh = c->d / c->H; c->N = cfg->batch * cfg->seq;
   c->eb = cfg->dtype == IL_F32 ? 4 : 2;
+  c->Lh = cfg->head_blocks;
   c->stream = (hipStream_t)cfg->stream;
   c->main_stream = c->stream;
   rc = build_plan(c->K, cfg->n, cfg->route, c->plan);
@@ -710,9 +734,19 @@ int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets,
     c->stream = c->side;
     swap.on = true;
   }
+  // the head's own blocks (App. B: the auxiliary network is Transformer blocks and an output matrix)
+  const float *y = x_k;
+  for (int l = 0; l < c->Lh; ++l) {
+    const size_t bi = (size_t)(k - 1) * c->Lh + l;
+    const BlockSave &s = c->hsave[bi];
+    float *yout = l == c->Lh - 1 ? c->hy : c->hsave[bi + 1].xs;
+    int rc = block_forward(c, c->hboff[bi], s, y, l == 0 ? s.xs : nullptr, yout);
+    if (rc) return rc;
+    y = yout;
+  }
   {
     Scope sc(c, KC_MISC, 0, (double)N * d * (4 + eb));
-    IL_TRY(convert_f32(dt, x_k, c->xb, (size_t)N * d, c->stream));
+    IL_TRY(convert_f32(dt, y, c->xb, (size_t)N * d, c->stream));
   }
   float *dx = c->dxh + (size_t)(k - 1) * N * d;
   for (int r0 = 0, chunk = 0; r0 < N; r0 += c->Nc, ++chunk) {
@@ -753,6 +787,31 @@ int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets,
   {
     Scope sc(c, KC_MISC, 0, (double)N * 4);
     IL_TRY(sum_scalar(c->rowloss, N, 1.f / N, loss_out, c->stream));
+  }
+  if (c->Lh) {
+    // dL_k/dy goes back through the head's blocks as a single stream of weight 1 in a slot of its own;
+    // what arrives at x_k replaces it as the head's gradient stream.
+    const size_t nd = (size_t)N * d;
+    const int slot = c->plan.nslots;
+    float *Gh = c->G + (size_t)slot * nd;
+    {
+      Scope sc(c, KC_MISC, 0, (double)nd * (8 + eb));
+      IL_TRY(stream_inject(dt, dx, Gh, c->Gb + (size_t)slot * nd * eb, nd, 0, c->stream));
+    }
+    Run r;
+    r.s0 = slot; r.cnt = 1; r.wt[0] = 1.f; r.nweighted = 1; r.first_weighted = 0; r.wscale = 1.f; r.acc = 0;
+    struct Inline { il_ctx *c; bool old; ~Inline() { c->tail_inline = old; } } guard{c, c->tail_inline};
+    c->tail_inline = true;  // already off the caller's stream: the block tails run in line
+    for (int l = c->Lh - 1; l >= 0; --l) {
+      const size_t bi = (size_t)(k - 1) * c->Lh + l;
+      int rc = block_backward(c, r, c->hboff[bi], c->hsave[bi]);
+      if (rc) return rc;
+    }
+    StreamWeights one;
+    memset(&one, 0, sizeof(one));
+    one.w[0] = 1.f;
+    Scope sc(c, KC_MISC, 0, (double)nd * 8);
+    IL_TRY(stream_combine(Gh, nd, 1, one, dx, nd, 0, c->stream));
   }
   if (swap.on) {
     IL_TRY(hipEventRecord(c->ev_head[k], c->side));

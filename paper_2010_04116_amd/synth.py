@@ -54,8 +54,9 @@ WORKLOADS: Dict[str, Workload] = {
     "many_head": Workload("many_head", "bf16", K=8, L=3, d=1024, H=16, m=4096, V=32768, B=8, T=512, n=3),
     "large": Workload("large", "bf16", K=6, L=6, d=2048, H=16, m=8192, V=50304, B=4, T=1024, n=2),
     # the shape of the paper's own Transformer modules (Sec. 4.3, App. B: 6 blocks per module, d = 1024,
-    # 4 attention heads -> head width 256, sequences of 128), one accelerator's worth of batch
-    "paper": Workload("paper", "bf16", K=4, L=6, d=1024, H=4, m=4096, V=32768, B=32, T=128, n=2),
+    # 4 attention heads -> head width 256, sequences of 128, auxiliary heads of 2 blocks + output matrix),
+    # one accelerator's worth of batch
+    "paper": Workload("paper", "bf16", K=4, L=6, d=1024, H=4, m=4096, V=32768, B=32, T=128, n=2, Lh=2),
 }
 PARAM_SEED = 20100411
 TOKEN_SEED = 20100511

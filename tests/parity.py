@@ -44,6 +44,11 @@ def compare(w, got, ref, label=""):
         e = rel(got["head_grads"][k], ref["head_grads"][k])
         assert e <= tol["grad"], f"{label} head {k + 1}: rel err {e:.3e}"
         worst["w_head"] = max(worst.get("w_head", 0), e)
+        for l in range(w.Lh):                                  # the head's own blocks
+            for name in synth.BLOCK_TENSORS:
+                e = rel(got["head_block_grads"][k][l][name], ref["head_block_grads"][k][l][name])
+                assert e <= tol["grad"], f"{label} head {k + 1} block {l + 1} {name}: rel err {e:.3e}"
+                worst["head_" + name] = max(worst.get("head_" + name, 0), e)
     if np.linalg.norm(ref["dx0"]) > 0:
         e = rel(got["dx0"], ref["dx0"])
         assert e <= tol["grad"], f"{label} dx0: rel err {e:.3e}"

@@ -65,6 +65,25 @@ def test_fp32_model_width_256():
     say("worst", compare(w, got, ref, "w256"))
 
 
+@pytest.mark.parametrize("route", ["window_sum", "mean_local_far"])
+@pytest.mark.parametrize("Lh", [1, 2])
+def test_fp32_heads_with_blocks(Lh, route):
+    """Auxiliary heads of Lh Transformer blocks + output matrix (the paper's Transformer heads, App. B)."""
+    w = TINY.with_(Lh=Lh, n=2, K=3)
+    say("case fp32 block heads Lh =", Lh, route)
+    got, ref = run_both(w, seed=9, route=route)
+    say("worst", compare(w, got, ref, f"Lh={Lh} {route}"))
+
+
+def test_bf16_heads_with_blocks():
+    w = synth.Workload("small_qh", "bf16", K=3, L=1, d=256, H=4, m=1024, V=2048, B=2, T=128, n=2, Lh=2)
+    say("case bf16 block heads")
+    got, ref = run_both(w, seed=10)
+    say("worst", compare(w, got, ref, "small_qh"))
+    got2, _ = run_both(w, seed=10)                           # heads on the side stream: reproducible
+    assert np.array_equal(got["losses"], got2["losses"]) and np.array_equal(got["dx0"], got2["dx0"])
+
+
 def test_head_chunking_does_not_change_results():
     w = TINY
     params, x0, tgt = make_inputs(w)
