@@ -50,6 +50,12 @@ def test_size_query_and_param_count():
         assert gb == binding.param_count(w) * 4
         assert wb > 0 and wb % 256 == 0
     assert binding.param_count(synth.WORKLOADS["medium"]) == 24 * (12 * 1024 ** 2 + 13 * 1024) + 4 * 1024 * 32768
+    # the paper-shaped workload: 4 heads of two blocks each on top of the 24 trunk blocks
+    assert binding.param_count(synth.WORKLOADS["paper"]) == 32 * (12 * 1024 ** 2 + 13 * 1024) + 4 * 1024 * 32768
+    # a fp32 head width of 256 has no kernel
+    cfg = binding.make_config(synth.WORKLOADS["paper"].with_(dtype="f32"))
+    ctx = C.c_void_p()
+    assert binding.load().il_init(C.byref(cfg), C.byref(ctx)) == binding.IL_E_SHAPE
 
 
 def test_misuse_returns_status_codes():
@@ -60,7 +66,8 @@ def test_misuse_returns_status_codes():
     for field, val, want in [("n", 0, binding.IL_E_ARG), ("n", 5, binding.IL_E_ARG),
                              ("dtype", 7, binding.IL_E_ARG), ("route", 9, binding.IL_E_ARG),
                              ("n_heads", 3, binding.IL_E_SHAPE), ("d_model", 4096, binding.IL_E_SHAPE),
-                             ("K", 0, binding.IL_E_ARG)]:
+                             ("K", 0, binding.IL_E_ARG), ("head_blocks", -1, binding.IL_E_ARG),
+                             ("reserved", 1, binding.IL_E_ARG)]:
         cfg = binding.make_config(w)
         setattr(cfg, field, val)
         assert lib.il_init(C.byref(cfg), C.byref(ctx)) == want, field
