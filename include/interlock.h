@@ -156,6 +156,17 @@ int il_head_xent(il_ctx *ctx, int32_t k, const float *x_k, const int32_t *target
  */
 int il_stage_backward_nwise(il_ctx *ctx, int32_t k, float *dx0_out);
 
+/*
+ * Micro-batching (Sec. 3.1: n-wise training combined with GPipe-style micro-batches).  With
+ * accumulate != 0 every parameter gradient written by the following steps is ADDED to what
+ * `grads` holds instead of overwriting it, and every gradient is multiplied by grad_scale
+ * (1/M for the mean over M equal micro-batches; losses are reported unscaled).  The first
+ * micro-batch of a mini-batch runs with accumulate = 0.  dx0_out is always overwritten (it
+ * belongs to the micro-batch's own tokens).  Call between steps.  IL_E_ARG for a NULL context or
+ * a grad_scale that is not positive and finite.
+ */
+int il_set_accumulation(il_ctx *ctx, int32_t accumulate, float grad_scale);
+
 /* Release the context (host memory and HIP events only; no device buffer is freed). */
 int il_free(il_ctx *ctx);
 
@@ -252,6 +263,23 @@ double il_lr_schedule(int64_t step, int32_t d_model, int32_t warmup_steps);
  */
 int il_adam_step(int32_t dtype, void *params, float *master, const float *grads, float *m, float *v,
                  size_t count, int64_t step, float lr, float beta1, float beta2, float eps, void *stream);
+
+/* ---- timing model of the paper (Sec. 3.1, App. C; host arithmetic) ------------------- */
+
+/*
+ * Time per mini-batch on A accelerators in sequence with M micro-batches and window N (clamped to
+ * A), slot cost c(M) = c0 + c1/M:
+ *   M = 1:                      2 N M c(M)
+ *   M = 2, or A >= 2N - 1:      (N + 1) M c(M)
+ *   otherwise (M > 2):          (2 + A - N) M c(M) + 2 (2N - A - 1) c(M)
+ * N = A is end-to-end training (GPipe for M >= 2), N = 1 local learning.  NaN for non-positive
+ * arguments.
+ */
+double il_time_per_batch(int32_t A, int32_t M, int32_t N, double c0, double c1);
+
+/* The power of two M <= max_m that minimises il_time_per_batch (the smallest on ties); negative
+ * il_status for non-positive arguments. */
+int32_t il_optimal_microbatches(int32_t A, int32_t N, double c0, double c1, int32_t max_m);
 
 /* Static string for a status code. */
 const char *il_status_string(int status);

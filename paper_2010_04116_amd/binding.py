@@ -23,7 +23,8 @@ IL_F32, IL_BF16 = 0, 1
 ROUTES = {"window_sum": 0, "far_head": 1, "mean_local_far": 2}
 SYMBOLS = ("il_init", "il_stage_forward", "il_head_xent", "il_stage_backward_nwise", "il_free",
            "il_routing_plan", "il_profile_read", "il_status_string", "il_test_gemm", "il_lr_schedule",
-           "il_adam_step", "il_embed_forward", "il_embed_backward")
+           "il_adam_step", "il_embed_forward", "il_embed_backward", "il_set_accumulation",
+           "il_time_per_batch", "il_optimal_microbatches")
 
 
 class il_config(C.Structure):
@@ -70,10 +71,14 @@ def load():
                                  C.c_float, vp]
     lib.il_embed_forward.argtypes = [i32, vp, vp, vp, i32, i32, i32, i32, vp, vp]
     lib.il_embed_backward.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp]
+    lib.il_set_accumulation.argtypes = [vp, i32, C.c_float]
+    lib.il_time_per_batch.argtypes = [i32, i32, i32, C.c_double, C.c_double]
+    lib.il_time_per_batch.restype = C.c_double
+    lib.il_optimal_microbatches.argtypes = [i32, i32, C.c_double, C.c_double, i32]
     lib.il_status_string.argtypes = [C.c_int]
     lib.il_status_string.restype = C.c_char_p
     for name in SYMBOLS:
-        if name not in ("il_status_string", "il_lr_schedule"):
+        if name not in ("il_status_string", "il_lr_schedule", "il_time_per_batch"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -190,6 +195,21 @@ def il_embed_forward(dtype, wte, wpe, tokens, batch: int, seq: int, d_model: int
 def il_embed_backward(dx0, tokens, batch: int, seq: int, d_model: int, vocab: int, dwte, dwpe, stream=None):
     _check(load().il_embed_backward(_ptr(dx0), _ptr(tokens), batch, seq, d_model, vocab, _ptr(dwte), _ptr(dwpe),
                                     stream), "il_embed_backward")
+
+
+def il_set_accumulation(ctx, accumulate: bool, grad_scale: float = 1.0):
+    _check(load().il_set_accumulation(ctx, int(accumulate), grad_scale), "il_set_accumulation")
+
+
+def il_time_per_batch(A: int, M: int, N: int, c0: float = 0.025, c1: float = 1.279) -> float:
+    return float(load().il_time_per_batch(A, M, N, c0, c1))
+
+
+def il_optimal_microbatches(A: int, N: int, c0: float = 0.025, c1: float = 1.279, max_m: int = 64) -> int:
+    rc = load().il_optimal_microbatches(A, N, c0, c1, max_m)
+    if rc < 0:
+        raise InterlockError(rc, "il_optimal_microbatches")
+    return rc
 
 
 def il_lr_schedule(step: int, d_model: int, warmup_steps: int = 4000) -> float:

@@ -176,6 +176,8 @@ struct il_ctx {
   std::vector<BlockOff> hboff;     // K*Lh: the heads' own blocks
   std::vector<BlockSave> hsave;    // K*Lh
   float *hy = nullptr;             // output of a head's last block, fp32 [N,d]
+  int accumulate = 0;              // micro-batching: add into grads instead of overwriting
+  float grad_scale = 1.f;          // ... and scale every gradient (applied to dlogits)
   bool tail_inline = false;        // block_backward is running on the side stream already (inside a head)
   float *G; char *Gb;              // stream slots [nslots][N,d]
   char *DU, *DH, *DQKV, *YS[4]; float *dsum, *partials[6], *skws; size_t skws_floats; ColsumJobs jobs;
@@ -438,7 +440,7 @@ int linear_wgrad(il_ctx *c, const Run &cp, const void *x, const void *dy, int Ki
     }
     c->pending.job[c->pending.count] = jb;
     c->pending_out[c->pending.count] = Gr(c, b_off);
-    c->pending_acc[c->pending.count] = cp.acc;
+    c->pending_acc[c->pending.count] = cp.acc | c->accumulate;
     c->pending_bytes += (double)(in_place ? 1 : cp.nweighted + 1) * c->N * Nout * c->eb;
     ++c->pending.count;
     if (c->pending.count == kMaxSumColsumJobs) {
@@ -450,7 +452,7 @@ int linear_wgrad(il_ctx *c, const Run &cp, const void *x, const void *dy, int Ki
   g.A = x; g.lda = Kin; g.a_kmajor = 1;
   g.B = dys; g.ldb = Nout; g.b_kmajor = 1;
   g.M = Kin; g.N = Nout; g.K = c->N;
-  g.epi = EPI_WGRAD; g.C = Gr(c, w_off); g.ldc = Nout; g.scale = 1.f; g.beta = cp.acc;
+  g.epi = EPI_WGRAD; g.C = Gr(c, w_off); g.ldc = Nout; g.scale = 1.f; g.beta = cp.acc | c->accumulate;
   out[(*nout)++] = g;
   return IL_OK;
 }
@@ -504,7 +506,8 @@ int ln_bwd(il_ctx *c, const Run &cp, const void *dy, const float *x, const float
   Scope sc(c, KC_LN_BWD, 0, (double)rows * c->d * (c->eb + 8 + c->eb) + (double)c->N * c->d * 4);
   IL_TRY(ln_backward_residual(c->cfg.dtype, dy, x, stats, P(c, g_off), rows, c->N, c->d, G, Gb, sw,
                               c->partials[slot], &nblk, c->stream));
-  if (cp.nweighted) c->jobs.job[c->jobs.count++] = ColsumJob{c->partials[slot], nblk, 2 * c->d, Gr(c, g_off), cp.acc};
+  if (cp.nweighted) c->jobs.job[c->jobs.count++] = ColsumJob{c->partials[slot], nblk, 2 * c->d, Gr(c, g_off),
+                                                              cp.acc | c->accumulate};
   return IL_OK;
 }
 
@@ -762,7 +765,7 @@ int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets,
     }
     {
       Scope sc(c, KC_XENT, 0, 2.0 * rows * V * eb);
-      IL_TRY(xent_rows(dt, c->Z, targets + r0, rows, V, 1.f / N, c->rowloss + r0, c->stream));
+      IL_TRY(xent_rows(dt, c->Z, targets + r0, rows, V, c->grad_scale / N, c->rowloss + r0, c->stream));
     }
     g = base_args();  // dx = dz W_h^T
     g.A = c->Z; g.lda = V; g.a_kmajor = 0;
@@ -778,7 +781,7 @@ int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets,
     g.A = xc; g.lda = d; g.a_kmajor = 1;
     g.B = c->Z; g.ldb = V; g.b_kmajor = 1;
     g.M = d; g.N = V; g.K = rows; g.epi = EPI_WGRAD; g.C = Gr(c, c->hoff[k - 1]); g.ldc = V;
-    g.beta = chunk > 0;
+    g.beta = chunk > 0 || c->accumulate;
     {
       Scope sc(c, KC_GEMM_HEAD, 2.0 * rows * V * d, gemm_bytes(c, g));
       IL_TRY(gemm(c, g));
@@ -917,6 +920,13 @@ int il_test_gemm(int32_t dtype, const void *A, const void *B, int32_t M, int32_t
   g.bias = bias; g.res = res; g.aux = aux; g.aux_wrap = aux_wrap; g.scale = scale; g.beta = beta; g.tile = tile;
   const hipError_t e = dtype == IL_F32 ? gemm_f32(g, (hipStream_t)stream) : gemm_bf16(g, (hipStream_t)stream);
   return e == hipSuccess ? IL_OK : (e == hipErrorInvalidValue ? IL_E_SHAPE : IL_E_HIP);
+}
+
+int il_set_accumulation(il_ctx *c, int32_t accumulate, float grad_scale) {
+  if (!c || !(grad_scale > 0.f) || !std::isfinite(grad_scale)) return IL_E_ARG;
+  c->accumulate = accumulate ? 1 : 0;
+  c->grad_scale = grad_scale;
+  return IL_OK;
 }
 
 int il_free(il_ctx *c) {

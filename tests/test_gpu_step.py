@@ -4,6 +4,7 @@ import sys
 import numpy as np
 import pytest
 
+from oracle import interlock as O
 from paper_2010_04116_amd import binding, synth
 from parity import compare, make_inputs, run_both
 
@@ -82,6 +83,35 @@ def test_bf16_heads_with_blocks():
     say("worst", compare(w, got, ref, "small_qh"))
     got2, _ = run_both(w, seed=10)                           # heads on the side stream: reproducible
     assert np.array_equal(got["losses"], got2["losses"]) and np.array_equal(got["dx0"], got2["dx0"])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_micro_batches_accumulate_to_the_full_batch_gradient(dtype):
+    """Two micro-batches of half the sequences each, the second accumulating, both scaled by 1/2:
+    the gradients of the whole mini-batch (the loss is a mean over positions, sequences are
+    independent), against the oracle on the full batch."""
+    if dtype == "f32":
+        w = TINY.with_(B=4, n=2, Lh=1)
+    else:
+        w = synth.Workload("mb", "bf16", K=3, L=1, d=256, H=4, m=512, V=1024, B=4, T=64, n=2)
+    say("case micro-batching", dtype)
+    params, x0, tgt = make_inputs(w, seed=11)
+    ref = O.nwise_streams(params, x0, tgt, w.B, w.T, w.H, w.n)
+    half = w.with_(B=w.B // 2)
+    st = binding.Step(half, binding.pack_params(w, params))
+    losses = []
+    for mb in range(2):
+        rows = slice(mb * half.N, (mb + 1) * half.N)
+        st.set_inputs(x0[rows], tgt[mb * half.B:(mb + 1) * half.B])
+        binding.il_set_accumulation(st.ctx, mb > 0, 0.5)
+        st.run()
+        losses.append(st.results()["losses"])
+    got = st.results()
+    st.close()
+    got["losses"] = 0.5 * (losses[0] + losses[1])
+    got["dx0"] = ref["dx0"] * 0                      # belongs to each micro-batch; not compared here
+    ref = dict(ref, dx0=ref["dx0"] * 0)
+    say("worst", compare(w, got, ref, "micro-batches"))
 
 
 def test_head_chunking_does_not_change_results():

@@ -132,3 +132,19 @@ def test_lr_schedule_and_adam_misuse_without_a_gpu():
     assert call(master=fake) == binding.IL_E_ARG                # fp32 mode takes no master copy
     assert call(dtype=binding.IL_BF16) == binding.IL_E_ARG      # bf16 mode needs one
     assert call(grads=C.c_void_p(4100)) == binding.IL_E_SHAPE   # misaligned
+
+
+def test_timing_model_host_functions_match_the_oracle():
+    from oracle import timing as Tm
+    for A in range(1, 33):
+        for N in (1, 2, 3, 5, 8, 40):
+            for M in (1, 2, 3, 4, 8, 16, 64):
+                assert binding.il_time_per_batch(A, M, N) == pytest.approx(Tm.time_per_batch(A, M, N), rel=1e-14)
+            assert binding.il_optimal_microbatches(A, N) == Tm.optimal_microbatches(A, N)
+    assert binding.il_time_per_batch(4, 8, 2, 0.1, 2.0) == pytest.approx(Tm.time_per_batch(4, 8, 2, 0.1, 2.0))
+    import math
+    assert math.isnan(binding.il_time_per_batch(0, 1, 1))
+    with pytest.raises(binding.InterlockError):
+        binding.il_optimal_microbatches(4, 0)
+    lib = binding.load()
+    assert lib.il_set_accumulation(None, 1, 0.5) == binding.IL_E_ARG
