@@ -266,7 +266,7 @@ def main():
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); depthwise sharding "
-                 "across GPUs is described in DESIGN.md and not built")
+                 "across GPUs (one component per GPU, point-to-point activations and gradient streams) is not built")
     if int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: launched with WORLD_SIZE > 1; this build runs on exactly one GPU")
 
