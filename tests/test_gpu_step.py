@@ -66,7 +66,7 @@ def test_fp32_model_width_256():
     say("worst", compare(w, got, ref, "w256"))
 
 
-@pytest.mark.parametrize("route", ["window_sum", "mean_local_far"])
+@pytest.mark.parametrize("route", ["window_sum", "mean_local_far", "far_head"])
 @pytest.mark.parametrize("Lh", [1, 2])
 def test_fp32_heads_with_blocks(Lh, route):
     """Auxiliary heads of Lh Transformer blocks + output matrix (the paper's Transformer heads, App. B)."""
