@@ -301,7 +301,7 @@ def nwise_definition(params, x0, targets, B, T, H, n, route="window_sum", eps=1e
             _axpy(acc[k - 1], w[k - 1, j - 1], gr)
         dx0 += w[0, j - 1] * g
     out = dict(losses=losses, comp_grads=acc, head_grads=dheads, dx0=dx0,
-               head_block_grads=dhblocks)
+               head_block_grads=dhblocks, x=xs)
     if return_table:
         out["table"] = table
     return out
@@ -333,4 +333,4 @@ def nwise_streams(params, x0, targets, B, T, H, n, route="window_sum", eps=1e-5)
     for j, g in live.items():
         dx0 += w[0, j - 1] * g
     return dict(losses=losses, comp_grads=acc, head_grads=dheads, dx0=dx0,
-                head_block_grads=dhblocks, backward_passes=passes[::-1])
+                head_block_grads=dhblocks, backward_passes=passes[::-1], x=xs)

@@ -209,9 +209,15 @@ struct GemmBatch {
   GemmArgs p[kMaxBatch];
 };
 
-template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGE, bool AKM, bool BKM, int EPI>
+// ALT: the wavefronts take turns at loading.  In step kt only one half of them (one wavefront per
+// SIMD) issues the direct loads of tile kt+1; their own LDS reads then queue behind those loads, but
+// the other half - which shares the SIMDs - starts multiplying at once, so the matrix unit works
+// through the time the loads are in flight.  The halves swap roles every step.
+template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGE, bool AKM, bool BKM, int EPI, bool ALT = false>
 __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmBatch batch) {
   constexpr int NT = 64 * WGM * WGN;
+  constexpr int NL = ALT ? NT / 2 : NT;  // threads that share the loading of one tile
+  static_assert(!ALT || (WGM * WGN == 8 && NSTAGE == 2), "two wavefronts per SIMD take turns");
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int MI = WTM / 32, NI = WTN / 32;
   constexpr int ABYTES = BM * BKT * 2, STAGE = (BM + BN) * BKT * 2;
@@ -240,19 +246,22 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmBatch batc
   const int m0 = tm * BM, n0 = tn * BN;
 
   const BufRsrc ra = make_rsrc(g.A, g.a_bytes), rb = make_rsrc(g.B, g.b_bytes);
-  typedef DmaTile<BM, BKT, AKM, NT> TA;
-  typedef DmaTile<BN, BKT, BKM, NT> TB;
+  typedef DmaTile<BM, BKT, AKM, NL> TA;
+  typedef DmaTile<BN, BKT, BKM, NL> TB;
   TA la;
   TB lb;
-  la.init(m0, g.M, g.lda, t);
-  lb.init(n0, g.N, g.ldb, t);
+  la.init(m0, g.M, g.lda, t % NL);
+  lb.init(n0, g.N, g.ldb, t % NL);
+  const int lwave = wave % (NL / 64);   // position of this wavefront among the loaders of a tile
+  const int lgroup = wave / (NL / 64);  // ALT: which half it belongs to (else 0)
   constexpr int LPS = TA::NLD + TB::NLD;  // loads per thread per K step
   const int kb0 = g.k_end > 0 ? g.k_begin : 0, ke = g.k_end > 0 ? g.k_end : g.K;
   const int nk = (ke - kb0 + BKT - 1) / BKT;
   auto issue = [&](int kt) {
+    if (ALT && lgroup != (kt & 1)) return;  // not this half's turn (uniform per wavefront)
     char *st = smem + (kt % NSTAGE) * STAGE;
-    la.issue(ra, st, wave, kb0 + kt * BKT, ke);
-    lb.issue(rb, st + ABYTES, wave, kb0 + kt * BKT, ke);
+    la.issue(ra, st, lwave, kb0 + kt * BKT, ke);
+    lb.issue(rb, st + ABYTES, lwave, kb0 + kt * BKT, ke);
   };
 
   floatx16 acc[MI][NI];
@@ -299,7 +308,7 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmBatch batc
 
 thread_local const KernelTimer *tl_timer = nullptr;  // armed by gemm_time_next()
 
-template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGE, bool AKM, bool BKM, int EPI>
+template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGE, bool AKM, bool BKM, int EPI, bool ALT = false>
 hipError_t launch_dma(GemmBatch &b, hipStream_t s) {
   int tiles = 0;
   for (int i = 0; i < b.count; ++i) {
@@ -308,10 +317,10 @@ hipError_t launch_dma(GemmBatch &b, hipStream_t s) {
   }
   if (const KernelTimer *t = tl_timer) {
     tl_timer = nullptr;
-    hipExtLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, BKT, NSTAGE, AKM, BKM, EPI>), dim3(tiles),
+    hipExtLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, BKT, NSTAGE, AKM, BKM, EPI, ALT>), dim3(tiles),
                           dim3(64 * WGM * WGN), 0, s, t->start, t->stop, 0, b);
   } else {
-    hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, BKT, NSTAGE, AKM, BKM, EPI>), dim3(tiles),
+    hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, BKT, NSTAGE, AKM, BKM, EPI, ALT>), dim3(tiles),
                        dim3(64 * WGM * WGN), 0, s, b);
   }
   return hipGetLastError();
@@ -326,7 +335,7 @@ hipError_t pick_tile(GemmBatch &b, hipStream_t s) {
   }
   switch (b.p[0].tile) {
     case 1: return launch_dma<256, 256, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
-    case 2: return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI>(b, s);
+    case 2: return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI, true>(b, s);
     case 3: return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
     case 4: return launch_dma<64, 64, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
     default: break;
@@ -335,7 +344,7 @@ hipError_t pick_tile(GemmBatch &b, hipStream_t s) {
   // (8 wavefronts) wins; below that the 128x128 tile, two workgroups per CU, keeps more CUs busy;
   // and when even those leave CUs idle, 64x64 tiles (four workgroups per CU) shorten each
   // workgroup's K loop, which is what bounds such a launch.
-  if (t256 >= 160) return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI>(b, s);
+  if (t256 >= 160) return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI, true>(b, s);
   if (t128 >= 256) return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
   return launch_dma<64, 64, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
 }

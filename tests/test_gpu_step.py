@@ -313,7 +313,7 @@ def _sampled_full_size(name, seed):
     got = binding.run_step(w, params, x0, tgt)
     say("oracle on sequence 0")
     ref = O.nwise_streams(params, x0[:w.T].astype(np.float64), tgt[:1], 1, w.T, w.H, w.n)
-    comps, heads, xs, *_ = O.forward_all(params, x0[:w.T].astype(np.float64), tgt[:1], 1, w.T, w.H)
+    xs = ref["x"]                               # the component outputs of the oracle's one forward pass
     for k in range(w.K):
         e = np.linalg.norm(got["x"][k + 1][:w.T] - xs[k]) / np.linalg.norm(xs[k])
         assert e <= 1e-2, f"{name}: x_{k + 1} rows of sequence 0: rel err {e:.3e}"
