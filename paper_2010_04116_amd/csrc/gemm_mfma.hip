@@ -209,15 +209,18 @@ struct GemmBatch {
   GemmArgs p[kMaxBatch];
 };
 
-// ALT: the wavefronts take turns at loading.  In step kt only one half of them (one wavefront per
-// SIMD) issues the direct loads of tile kt+1; their own LDS reads then queue behind those loads, but
-// the other half - which shares the SIMDs - starts multiplying at once, so the matrix unit works
-// through the time the loads are in flight.  The halves swap roles every step.
-template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGE, bool AKM, bool BKM, int EPI, bool ALT = false>
-__global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmBatch batch) {
-  constexpr int NT = 64 * WGM * WGN;
-  constexpr int NL = ALT ? NT / 2 : NT;  // threads that share the loading of one tile
-  static_assert(!ALT || (WGM * WGN == 8 && NSTAGE == 2), "two wavefronts per SIMD take turns");
+// Who issues the direct loads.  A wavefront's LDS operations complete in issue order and a direct
+// load is one of them, so a wavefront that loads the next tile and then reads fragments of the
+// current one waits for its own loads.  With LOADERS four extra wavefronts (one per SIMD) do
+// nothing but load, NSTAGE-1 tiles ahead, and the multiplying wavefronts never have a load in
+// their LDS queue; without, every wavefront loads its share and then multiplies (the cheaper
+// arrangement when many small workgroups share a CU and cover for each other).
+constexpr int kLoaderWaves = 4;
+template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGE, bool AKM, bool BKM, int EPI, bool LOADERS = false>
+__global__ __launch_bounds__(64 * (WGM * WGN + (LOADERS ? kLoaderWaves : 0))) void gemm_dma_kernel(GemmBatch batch) {
+  constexpr bool SPEC = LOADERS;
+  constexpr int NC = 64 * WGM * WGN;                // multiplying threads
+  constexpr int NL = SPEC ? 64 * kLoaderWaves : NC;  // threads that share the loading of one tile
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int MI = WTM / 32, NI = WTN / 32;
   constexpr int ABYTES = BM * BKT * 2, STAGE = (BM + BN) * BKT * 2;
@@ -252,13 +255,12 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmBatch batc
   TB lb;
   la.init(m0, g.M, g.lda, t % NL);
   lb.init(n0, g.N, g.ldb, t % NL);
-  const int lwave = wave % (NL / 64);   // position of this wavefront among the loaders of a tile
-  const int lgroup = wave / (NL / 64);  // ALT: which half it belongs to (else 0)
+  const int lwave = wave % (NL / 64);             // position of this wavefront among the loaders of a tile
+  const bool loader = SPEC && wave >= WGM * WGN;  // this wavefront only loads (uniform)
   constexpr int LPS = TA::NLD + TB::NLD;  // loads per thread per K step
   const int kb0 = g.k_end > 0 ? g.k_begin : 0, ke = g.k_end > 0 ? g.k_end : g.K;
   const int nk = (ke - kb0 + BKT - 1) / BKT;
   auto issue = [&](int kt) {
-    if (ALT && lgroup != (kt & 1)) return;  // not this half's turn (uniform per wavefront)
     char *st = smem + (kt % NSTAGE) * STAGE;
     la.issue(ra, st, lwave, kb0 + kt * BKT, ke);
     lb.issue(rb, st + ABYTES, lwave, kb0 + kt * BKT, ke);
@@ -273,19 +275,43 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmBatch batc
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   // K steps kt .. kt+NSTAGE-2 are in flight while step kt is multiplied; one barrier per step:
-  // it publishes step kt (every thread waited for its own loads of it) and retires the buffer
-  // of step kt-1, which the loads issued right after it overwrite.
+  // it publishes step kt (every loading thread waited for its own loads of it) and retires the
+  // buffer of step kt-1, which the loads issued right after it overwrite.
+  if (!SPEC || loader) {
 #pragma unroll
-  for (int s = 0; s < NSTAGE - 1; ++s)
-    if (s < nk) issue(s);
+    for (int s = 0; s < NSTAGE - 1; ++s)
+      if (s < nk) issue(s);
+  }
+  if (loader) {
+    // the same barriers as the multiplying wavefronts, through the epilogue's, then done
+    for (int kt = 0; kt < nk; ++kt) {
+      if (nk - 1 - kt >= NSTAGE - 2)
+        wait_vmcnt<(NSTAGE - 2) * LPS>();
+      else
+        wait_vmcnt<0>();
+      __syncthreads();
+      if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < MI; ++i) {
+      __syncthreads();
+      __syncthreads();
+    }
+    return;
+  }
 
   for (int kt = 0; kt < nk; ++kt) {
-    if (nk - 1 - kt >= NSTAGE - 2)
-      wait_vmcnt<(NSTAGE - 2) * LPS>();
-    else
-      wait_vmcnt<0>();
+    if constexpr (!SPEC) {
+      if (nk - 1 - kt >= NSTAGE - 2)
+        wait_vmcnt<(NSTAGE - 2) * LPS>();
+      else
+        wait_vmcnt<0>();
+    }
     __syncthreads();
-    if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
+    if constexpr (!SPEC) {
+      if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
+    }
     const char *sa = smem + (kt % NSTAGE) * STAGE;
     const char *sb = sa + ABYTES;
 #pragma unroll
@@ -308,44 +334,51 @@ __global__ __launch_bounds__(64 * WGM * WGN) void gemm_dma_kernel(GemmBatch batc
 
 thread_local const KernelTimer *tl_timer = nullptr;  // armed by gemm_time_next()
 
-template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGE, bool AKM, bool BKM, int EPI, bool ALT = false>
+template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGE, bool AKM, bool BKM, int EPI, bool LOADERS = false>
 hipError_t launch_dma(GemmBatch &b, hipStream_t s) {
   int tiles = 0;
   for (int i = 0; i < b.count; ++i) {
     tiles += ((b.p[i].M + BM - 1) / BM) * ((b.p[i].N + BN - 1) / BN);
     b.tile_end[i] = tiles;
   }
+  constexpr int nthreads = 64 * (WGM * WGN + (LOADERS ? kLoaderWaves : 0));
   if (const KernelTimer *t = tl_timer) {
     tl_timer = nullptr;
-    hipExtLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, BKT, NSTAGE, AKM, BKM, EPI, ALT>), dim3(tiles),
-                          dim3(64 * WGM * WGN), 0, s, t->start, t->stop, 0, b);
+    hipExtLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, BKT, NSTAGE, AKM, BKM, EPI, LOADERS>), dim3(tiles),
+                          dim3(nthreads), 0, s, t->start, t->stop, 0, b);
   } else {
-    hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, BKT, NSTAGE, AKM, BKM, EPI, ALT>), dim3(tiles),
-                       dim3(64 * WGM * WGN), 0, s, b);
+    hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, BKT, NSTAGE, AKM, BKM, EPI, LOADERS>), dim3(tiles),
+                       dim3(nthreads), 0, s, b);
   }
   return hipGetLastError();
 }
 
 template <bool AKM, bool BKM, int EPI>
 hipError_t pick_tile(GemmBatch &b, hipStream_t s) {
-  long t256 = 0, t128 = 0;
+  long t256 = 0, t128 = 0, t64 = 0;
   for (int i = 0; i < b.count; ++i) {
+    t64 += (long)((b.p[i].M + 63) / 64) * ((b.p[i].N + 63) / 64);
     t256 += (long)((b.p[i].M + 255) / 256) * ((b.p[i].N + 255) / 256);
     t128 += (long)((b.p[i].M + 127) / 128) * ((b.p[i].N + 127) / 128);
   }
   switch (b.p[0].tile) {
-    case 1: return launch_dma<256, 256, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
-    case 2: return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI, true>(b, s);
-    case 3: return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
+    case 1: return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI, true>(b, s);
+    case 2: return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI, true>(b, s);
+    case 3: return launch_dma<128, 128, 2, 2, 64, 4, AKM, BKM, EPI, true>(b, s);
     case 4: return launch_dma<64, 64, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
+    case 5: return launch_dma<64, 64, 2, 2, 64, 4, AKM, BKM, EPI, true>(b, s);
     default: break;
   }
-  // Measured on MI355X: with enough 256x256 tiles to cover most of the 256 CUs the large tile
-  // (8 wavefronts) wins; below that the 128x128 tile, two workgroups per CU, keeps more CUs busy;
-  // and when even those leave CUs idle, 64x64 tiles (four workgroups per CU) shorten each
-  // workgroup's K loop, which is what bounds such a launch.
+  // Measured on MI355X.  With enough 256x256 tiles to cover most of the 256 CUs the large tile
+  // wins (fewest operand bytes per flop).  Below that the 128x128 tile: two workgroups per CU with
+  // two stages when there are more tiles than CUs, one workgroup with four stages in flight when
+  // each CU gets at most one.  When even those leave CUs idle, 64x64 tiles shorten each workgroup's
+  // K loop, which is what bounds such a launch: up to five small workgroups per CU that cover
+  // for each other, or - if each CU gets only one - loader wavefronts and four stages again.
   if (t256 >= 160) return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI, true>(b, s);
-  if (t128 >= 256) return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
+  if (t128 > 256) return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI, true>(b, s);
+  if (t128 >= 208) return launch_dma<128, 128, 2, 2, 64, 4, AKM, BKM, EPI, true>(b, s);
+  if (t64 <= 256) return launch_dma<64, 64, 2, 2, 64, 4, AKM, BKM, EPI, true>(b, s);
   return launch_dma<64, 64, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
 }
 

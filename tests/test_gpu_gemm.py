@@ -7,7 +7,7 @@ import pytest
 from paper_2010_04116_amd import binding as b, synth
 
 pytestmark = pytest.mark.gpu
-TILES = [1, 2, 3, 4]
+TILES = [1, 2, 3, 4, 5]
 
 
 def _bf16(a):
@@ -97,7 +97,7 @@ def test_k_tail_and_tiny_sizes(tile):
     run_case(40, 72, 72, 1, 1, 6, tile, seed=33)
 
 
-@pytest.mark.parametrize("tile", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("tile", [0] + TILES)
 def test_multi_tile_shapes(tile):
     run_case(1024, 768, 512, 0, 1, 1, tile, seed=40)
     run_case(1024, 768, 512, 0, 0, 0, tile, seed=41)
@@ -127,7 +127,7 @@ def test_seeded_random_shapes_every_tile_choice():
     for case in range(36):
         M, N, K = (int(rng.choice(dims)) for _ in range(3))
         akm, bkm, epi = _COMBOS[case % len(_COMBOS)]
-        tile = [0, 1, 2, 3, 4][case % 5]
+        tile = [0, 1, 2, 3, 4, 5, 0][case % 7]
         print("case", case, M, N, K, akm, bkm, epi, "tile", tile, flush=True)
         run_case(M, N, K, akm, bkm, epi, tile, seed=1000 + case, beta=case & 1, scale=0.5 if case & 2 else 1.0)
 
