@@ -186,7 +186,7 @@ def test_bf16_paper_routes(route, n):
     say("worst", compare(w, got, ref, f"{route} n={n}"))
 
 
-@pytest.mark.parametrize("n", [1, 2])
+@pytest.mark.parametrize("n", [1, 2, 4])      # local, the benchmark's window, n = K (global backprop)
 def test_small_bf16_full_step(n):
     w = synth.WORKLOADS["small"].with_(n=n)
     say("case small bf16 n =", n)
