@@ -198,13 +198,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(DH > 64 ? 1
         }
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float mnew = fmaxf(m, mx);
-      const float alpha = exp2f(m - mnew);
+      const float alpha = __builtin_amdgcn_exp2f(m - mnew);
       float rs = 0.f;
 #pragma unroll
       for (int a = 0; a < NA; ++a)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const float p = exp2f(s[a][r] - mnew);
+          const float p = __builtin_amdgcn_exp2f(s[a][r] - mnew);
           s[a][r] = p;
           rs += p;
         }
@@ -252,10 +252,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(DH > 64 ? 1
 // grid (ceil(T/128), B*H, streams).  Same walk as the forward.  Also writes
 // dsum[q] = sum_i dO[q,i] O[q,i] for the dK/dV kernel.
 template <int DH>
-__global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ o,
-                                                        const bf16_t *__restrict__ d_o,
-                                                        const float *__restrict__ lse, int B, int T, int H,
-                                                        bf16_t *__restrict__ dqkv, float *__restrict__ dsum) {
+__device__ __forceinline__ void attn_bwd_dq_body(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ o,
+                                                 const bf16_t *__restrict__ d_o, const float *__restrict__ lse, int B,
+                                                 int T, int H, bf16_t *__restrict__ dqkv, float *__restrict__ dsum) {
   constexpr int BQ = 128, BKV = 64;
   constexpr int KT = BKV * DH * 2, STAGE = 2 * KT;  // K and V tiles as stored
   typedef TokTile<BKV, DH> Tile;
@@ -339,7 +338,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t *__restrict
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float p = exp2f(s[r] * sc2 - lq2);
+          float p = __builtin_amdgcn_exp2f(s[r] * sc2 - lq2);
           if (diag) {
             const int kv = kv0 + 32 * a + 8 * (r >> 2) + 4 * hh + (r & 3);
             if (kv > q || kv >= T) p = 0.f;
@@ -380,11 +379,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t *__restrict
 // computed as S = Q K^T with the query index in the accumulator rows, so P and dS feed the
 // products dV^T = dO^T P and dK^T = Q^T dS directly from registers.
 template <int DH>
-__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t *__restrict__ qkv,
-                                                         const bf16_t *__restrict__ d_o,
-                                                         const float *__restrict__ lse,
-                                                         const float *__restrict__ dsum, int B, int T, int H,
-                                                         bf16_t *__restrict__ dqkv) {
+__device__ __forceinline__ void attn_bwd_dkv_body(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ d_o,
+                                                  const float *__restrict__ lse, const float *__restrict__ dsum, int B,
+                                                  int T, int H, bf16_t *__restrict__ dqkv) {
   constexpr int BKV = 128, BQ = 64;
   constexpr int QT = BQ * DH * 2;                 // one staged tile
   constexpr int STAGE = 2 * QT + 2 * BQ * 4;      // Q, dO as stored, lse, dsum
@@ -469,7 +466,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t *__restric
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = 4 * g + e;
-          float p = exp2f(s[r] * sc2 - lv4[e] * kLog2e);
+          float p = __builtin_amdgcn_exp2f(s[r] * sc2 - lv4[e] * kLog2e);
           if (diag) {
             const int qq = qa0 + 8 * g + 4 * hh + e;
             if (kv > qq || qq >= T) p = 0.f;
@@ -513,6 +510,38 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t *__restric
   }
 }
 
+// The kernels proper.  With at least two wavefronts per SIMD demanded, the register budget is the
+// 256 architectural VGPRs and the compiler keeps the MFMA accumulators there; without, it places
+// them in the accumulation registers and moves every score to a VGPR and back (a third of the
+// vector instructions at head width 64).  Head widths above 64 do not fit that budget.
+template <int DH>
+__global__ __launch_bounds__(256) void attn_bwd_dq_mfma(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ o,
+                                                        const bf16_t *__restrict__ d_o,
+                                                        const float *__restrict__ lse, int B, int T, int H,
+                                                        bf16_t *__restrict__ dqkv, float *__restrict__ dsum) {
+  attn_bwd_dq_body<DH>(qkv, o, d_o, lse, B, T, H, dqkv, dsum);
+}
+template <int DH>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void attn_bwd_dq_mfma_v(
+    const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ o, const bf16_t *__restrict__ d_o,
+    const float *__restrict__ lse, int B, int T, int H, bf16_t *__restrict__ dqkv, float *__restrict__ dsum) {
+  attn_bwd_dq_body<DH>(qkv, o, d_o, lse, B, T, H, dqkv, dsum);
+}
+template <int DH>
+__global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t *__restrict__ qkv,
+                                                         const bf16_t *__restrict__ d_o,
+                                                         const float *__restrict__ lse,
+                                                         const float *__restrict__ dsum, int B, int T, int H,
+                                                         bf16_t *__restrict__ dqkv) {
+  attn_bwd_dkv_body<DH>(qkv, d_o, lse, dsum, B, T, H, dqkv);
+}
+template <int DH>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void attn_bwd_dkv_mfma_v(
+    const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ d_o, const float *__restrict__ lse,
+    const float *__restrict__ dsum, int B, int T, int H, bf16_t *__restrict__ dqkv) {
+  attn_bwd_dkv_body<DH>(qkv, d_o, lse, dsum, B, T, H, dqkv);
+}
+
 }  // namespace
 
 hipError_t attention_forward_mfma(const void *qkv, int B, int T, int H, int dh, void *o, float *lse,
@@ -533,9 +562,9 @@ hipError_t attention_backward_mfma(const void *qkv, const void *o, const void *d
                                    int B, int T, int H, int dh, void *dqkv, float *dsum, hipStream_t s) {
   dim3 grid((T + 127) / 128, B * H, ns);
   if (dh == 64) {
-    hipLaunchKernelGGL(attn_bwd_dq_mfma<64>, grid, dim3(256), 0, s, (const bf16_t *)qkv, (const bf16_t *)o,
+    hipLaunchKernelGGL(attn_bwd_dq_mfma_v<64>, grid, dim3(256), 0, s, (const bf16_t *)qkv, (const bf16_t *)o,
                        (const bf16_t *)d_o, lse, B, T, H, (bf16_t *)dqkv, dsum);
-    hipLaunchKernelGGL(attn_bwd_dkv_mfma<64>, grid, dim3(256), 0, s, (const bf16_t *)qkv, (const bf16_t *)d_o, lse,
+    hipLaunchKernelGGL(attn_bwd_dkv_mfma_v<64>, grid, dim3(256), 0, s, (const bf16_t *)qkv, (const bf16_t *)d_o, lse,
                        dsum, B, T, H, (bf16_t *)dqkv);
   } else if (dh == 128) {
     hipLaunchKernelGGL(attn_bwd_dq_mfma<128>, grid, dim3(256), 0, s, (const bf16_t *)qkv, (const bf16_t *)o,
