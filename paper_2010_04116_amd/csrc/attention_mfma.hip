@@ -324,7 +324,7 @@ __device__ __forceinline__ void attn_bwd_dq_body(const bf16_t *__restrict__ qkv,
     }
     if (kv0 <= qw0 + 31) {
       const bool diag = kv0 + BKV - 1 > qw0 || kv0 + BKV > T;
-#pragma unroll
+#pragma unroll(DH > 64 ? 1 : 2)
       for (int a = 0; a < 2; ++a) {
         floatx16 s, dp;
 #pragma unroll
@@ -442,7 +442,7 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const bf16_t *__restrict__ qkv
     wait_vmcnt<0>();
     __syncthreads();
     if (qt + 1 < nqt) issue(qt + 1, smem + ((it + 1) & 1) * STAGE);
-#pragma unroll
+#pragma unroll(DH > 64 ? 1 : 2)
     for (int a = 0; a < BQ / 32; ++a) {
       const int qa0 = qb0 + 32 * a;
       if (qa0 + 31 < kvw0 || qa0 >= T) continue;  // every query of the sub-tile precedes every key
@@ -567,7 +567,7 @@ hipError_t attention_backward_mfma(const void *qkv, const void *o, const void *d
     hipLaunchKernelGGL(attn_bwd_dkv_mfma_v<64>, grid, dim3(256), 0, s, (const bf16_t *)qkv, (const bf16_t *)d_o, lse,
                        dsum, B, T, H, (bf16_t *)dqkv);
   } else if (dh == 128) {
-    hipLaunchKernelGGL(attn_bwd_dq_mfma<128>, grid, dim3(256), 0, s, (const bf16_t *)qkv, (const bf16_t *)o,
+    hipLaunchKernelGGL(attn_bwd_dq_mfma_v<128>, grid, dim3(256), 0, s, (const bf16_t *)qkv, (const bf16_t *)o,
                        (const bf16_t *)d_o, lse, B, T, H, (bf16_t *)dqkv, dsum);
     hipLaunchKernelGGL(attn_bwd_dkv_mfma<128>, grid, dim3(256), 0, s, (const bf16_t *)qkv, (const bf16_t *)d_o, lse,
                        dsum, B, T, H, (bf16_t *)dqkv);
