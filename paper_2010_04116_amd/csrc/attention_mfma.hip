@@ -99,9 +99,9 @@ struct TokTile {
 // ------------------------------------------------------------------ forward -------------
 // grid (ceil(T/128), B*H); 4 wavefronts, each owns 32 queries; key tiles of 64.
 template <int DH>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(DH > 64 ? 1 : 2, DH > 64 ? 1 : 2))) void attn_fwd_mfma(const bf16_t *__restrict__ qkv, int T, int H,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(DH > 128 ? 1 : 2, DH > 128 ? 1 : 2))) void attn_fwd_mfma(const bf16_t *__restrict__ qkv, int T, int H,
                                                      bf16_t *__restrict__ o, float *__restrict__ lse) {
-  constexpr int BQ = 128, BKV = 64, NA = BKV / 32;
+  constexpr int BQ = 128, BKV = DH > 128 ? 32 : 64, NA = BKV / 32;
   constexpr bool HOIST = DH <= 64;  // the wider head has no registers to spare for a whole tile of fragments
   constexpr int KT = BKV * DH * 2, STAGE = 2 * KT;
   typedef TokTile<BKV, DH> Tile;
