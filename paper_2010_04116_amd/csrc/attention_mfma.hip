@@ -17,6 +17,7 @@
 // the query tiles at or below the diagonal, the other owns a query tile and accumulates dQ.
 #include "common.h"
 #include "lds_dma.h"
+#include <type_traits>
 
 namespace il {
 namespace {
@@ -28,6 +29,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4v;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kNegBig = -1.0e30f;
+constexpr floatx16 kZero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
 __device__ inline uint4 ldg16(const bf16_t *p) { return *reinterpret_cast<const uint4 *>(p); }
 __device__ inline uint32_t pack2(float a, float b) {
@@ -175,8 +177,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(DH > 128 ? 
       floatx16 s[NA];
 #pragma unroll
       for (int a = 0; a < NA; ++a) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[a][r] = 0.f;
+        s[a] = kZero16;
 #pragma unroll
         for (int ks = 0; ks < DH / 16; ++ks)
           s[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(HOIST ? kf[HOIST ? a : 0][HOIST ? ks : 0] : Tile::rowfrag(sk, 32 * a, ks, lane),
@@ -184,18 +185,25 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(DH > 128 ? 
       }
       const bool diag = kv0 + BKV - 1 > qw0 || kv0 + BKV > T;
       float mx = kNegBig;
+      // the causal / end-of-sequence mask is compiled into the diagonal tiles' path only
+      auto scale_mask_max = [&](auto masked) {
 #pragma unroll
-      for (int a = 0; a < NA; ++a)
+        for (int a = 0; a < NA; ++a)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float v = s[a][r] * sc;
-          if (diag) {
-            const int kv = kv0 + 32 * a + 8 * (r >> 2) + 4 * hh + (r & 3);
-            if (kv > q || kv >= T) v = kNegBig;
+          for (int r = 0; r < 16; ++r) {
+            float v = s[a][r] * sc;
+            if constexpr (decltype(masked)::value) {
+              const int kv = kv0 + 32 * a + 8 * (r >> 2) + 4 * hh + (r & 3);
+              if (kv > q || kv >= T) v = kNegBig;
+            }
+            s[a][r] = v;
+            mx = fmaxf(mx, v);
           }
-          s[a][r] = v;
-          mx = fmaxf(mx, v);
-        }
+      };
+      if (DH > 128 || diag)  // (at head width 256 a second copy of the loop costs more in registers than it saves)
+        scale_mask_max(std::true_type{});
+      else
+        scale_mask_max(std::false_type{});
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float mnew = fmaxf(m, mx);
       const float alpha = __builtin_amdgcn_exp2f(m - mnew);
@@ -298,6 +306,7 @@ __device__ __forceinline__ void attn_bwd_dq_body(const bf16_t *__restrict__ qkv,
   const float sc = rsqrtf((float)DH);
   const float sc2 = sc * kLog2e;
   const float lq2 = (q < T) ? lse[((size_t)b * H + h) * T + q] * kLog2e : 0.f;
+  const float dsv_sc = dsv * sc;
 
   floatx16 dq[DH / 32];
 #pragma unroll
@@ -326,9 +335,7 @@ __device__ __forceinline__ void attn_bwd_dq_body(const bf16_t *__restrict__ qkv,
       const bool diag = kv0 + BKV - 1 > qw0 || kv0 + BKV > T;
 #pragma unroll(DH > 64 ? 1 : 2)
       for (int a = 0; a < 2; ++a) {
-        floatx16 s, dp;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+        floatx16 s = kZero16, dp = kZero16;  // a constant accumulator input costs no registers to clear
 #pragma unroll
         for (int ks = 0; ks < DH / 16; ++ks) {
           const bf16x8 kf = Tile::rowfrag(sk, 32 * a, ks, lane);
@@ -336,15 +343,21 @@ __device__ __forceinline__ void attn_bwd_dq_body(const bf16_t *__restrict__ qkv,
           s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks].v, s, 0, 0, 0);
           dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, gf[ks].v, dp, 0, 0, 0);
         }
+        auto probs = [&](auto masked) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float p = __builtin_amdgcn_exp2f(s[r] * sc2 - lq2);
-          if (diag) {
-            const int kv = kv0 + 32 * a + 8 * (r >> 2) + 4 * hh + (r & 3);
-            if (kv > q || kv >= T) p = 0.f;
+          for (int r = 0; r < 16; ++r) {
+            float p = __builtin_amdgcn_exp2f(s[r] * sc2 - lq2);
+            if constexpr (decltype(masked)::value) {
+              const int kv = kv0 + 32 * a + 8 * (r >> 2) + 4 * hh + (r & 3);
+              if (kv > q || kv >= T) p = 0.f;
+            }
+            s[r] = p * (dp[r] * sc - dsv_sc);  // dS^T
           }
-          s[r] = p * (dp[r] - dsv) * sc;  // dS^T
-        }
+        };
+        if (DH > 128 || diag)
+          probs(std::true_type{});
+        else
+          probs(std::false_type{});
 #pragma unroll
         for (int bq = 0; bq < 2; ++bq) {
           Frag pf;
@@ -446,9 +459,7 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const bf16_t *__restrict__ qkv
     for (int a = 0; a < BQ / 32; ++a) {
       const int qa0 = qb0 + 32 * a;
       if (qa0 + 31 < kvw0 || qa0 >= T) continue;  // every query of the sub-tile precedes every key
-      floatx16 s, dp;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+      floatx16 s = kZero16, dp = kZero16;
 #pragma unroll
       for (int ks = 0; ks < DH / 16; ++ks) {
         const bf16x8 qf = Tile::rowfrag(sq, 32 * a, ks, lane);
@@ -458,23 +469,29 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const bf16_t *__restrict__ qkv
       }
       const bool diag = qa0 < kvw0 + 31 || qa0 + 32 > T;
       floatx16 pr;
+      auto probs = [&](auto masked) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const float4 l4 = *reinterpret_cast<const float4 *>(sl + 32 * a + 8 * g + 4 * hh);
-        const float4 d4 = *reinterpret_cast<const float4 *>(sd + 32 * a + 8 * g + 4 * hh);
-        const float lv4[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+        for (int g = 0; g < 4; ++g) {
+          const float4 l4 = *reinterpret_cast<const float4 *>(sl + 32 * a + 8 * g + 4 * hh);
+          const float4 d4 = *reinterpret_cast<const float4 *>(sd + 32 * a + 8 * g + 4 * hh);
+          const float lv4[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int r = 4 * g + e;
-          float p = __builtin_amdgcn_exp2f(s[r] * sc2 - lv4[e] * kLog2e);
-          if (diag) {
-            const int qq = qa0 + 8 * g + 4 * hh + e;
-            if (kv > qq || qq >= T) p = 0.f;
+          for (int e = 0; e < 4; ++e) {
+            const int r = 4 * g + e;
+            float p = __builtin_amdgcn_exp2f(s[r] * sc2 - lv4[e] * kLog2e);
+            if constexpr (decltype(masked)::value) {
+              const int qq = qa0 + 8 * g + 4 * hh + e;
+              if ((DH <= 128 || diag) && (kv > qq || qq >= T)) p = 0.f;
+            }
+            pr[r] = p;
+            s[r] = p * (dp[r] - dv4[e]) * sc;  // dS
           }
-          pr[r] = p;
-          s[r] = p * (dp[r] - dv4[e]) * sc;  // dS
         }
-      }
+      };
+      if (DH > 128 || diag)
+        probs(std::true_type{});
+      else
+        probs(std::false_type{});
 #pragma unroll
       for (int bq = 0; bq < 2; ++bq) {
         Frag pf, sf;
