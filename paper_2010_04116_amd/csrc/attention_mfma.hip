@@ -468,13 +468,14 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const bf16_t *__restrict__ qkv
         dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf, vf[ks].v, dp, 0, 0, 0);
       }
       const bool diag = qa0 < kvw0 + 31 || qa0 + 32 > T;
-      floatx16 pr;
+      Frag pf[2], sf[2];  // P and dS of the sub-tile, packed to bf16 as they are produced
       auto probs = [&](auto masked) {
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const float4 l4 = *reinterpret_cast<const float4 *>(sl + 32 * a + 8 * g + 4 * hh);
           const float4 d4 = *reinterpret_cast<const float4 *>(sd + 32 * a + 8 * g + 4 * hh);
           const float lv4[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+          float p4[4], s4[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             const int r = 4 * g + e;
@@ -483,9 +484,13 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const bf16_t *__restrict__ qkv
               const int qq = qa0 + 8 * g + 4 * hh + e;
               if ((DH <= 128 || diag) && (kv > qq || qq >= T)) p = 0.f;
             }
-            pr[r] = p;
-            s[r] = p * (dp[r] - dv4[e]) * sc;  // dS
+            p4[e] = p;
+            s4[e] = p * (dp[r] - dv4[e]) * sc;  // dS
           }
+          pf[g >> 1].u[2 * (g & 1)] = pack2(p4[0], p4[1]);
+          pf[g >> 1].u[2 * (g & 1) + 1] = pack2(p4[2], p4[3]);
+          sf[g >> 1].u[2 * (g & 1)] = pack2(s4[0], s4[1]);
+          sf[g >> 1].u[2 * (g & 1) + 1] = pack2(s4[2], s4[3]);
         }
       };
       if (DH > 128 || diag)
@@ -494,18 +499,12 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const bf16_t *__restrict__ qkv
         probs(std::false_type{});
 #pragma unroll
       for (int bq = 0; bq < 2; ++bq) {
-        Frag pf, sf;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          pf.u[e] = pack2(pr[8 * bq + 2 * e], pr[8 * bq + 2 * e + 1]);
-          sf.u[e] = pack2(s[8 * bq + 2 * e], s[8 * bq + 2 * e + 1]);
-        }
 #pragma unroll
         for (int dt = 0; dt < DH / 32; ++dt) {
           const bf16x8 gt = Tile::trfrag(sg, 32 * a + 16 * bq, dt, lane);
           const bf16x8 qtf = Tile::trfrag(sq, 32 * a + 16 * bq, dt, lane);
-          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, pf.v, dv[dt], 0, 0, 0);
-          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qtf, sf.v, dk[dt], 0, 0, 0);
+          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, pf[bq].v, dv[dt], 0, 0, 0);
+          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qtf, sf[bq].v, dk[dt], 0, 0, 0);
         }
       }
     }
