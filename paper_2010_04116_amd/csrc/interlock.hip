@@ -473,15 +473,26 @@ int launch_wgrads(il_ctx *c, const GemmArgs *list, int n) {
   return IL_OK;
 }
 
-// Split-K factor for an fp32-output GEMM whose 128x128 tiles alone would leave CUs idle.
+// Split-K factor for an fp32-output GEMM (the head's dx: few output tiles, K = vocabulary).
+// Two ways to fill the chip are priced with measured per-K-step times and the better one is taken:
+// 128x128 tiles, two workgroups per CU (0.96 us per 64-deep step), split until about 512 tiles;
+// or 256x256 tiles, one per CU (1.6 us per step, 2.6x the flops), split until about 256 tiles.
+// gemm_bf16_batch then picks the matching tile from the tile counts of the split problem.
 int choose_splits(il_ctx *c, int M, int N, int K) {
-  const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
-  if (c->cfg.dtype != IL_BF16 || tiles >= 200) return 1;
-  long sp = 512 / tiles;
-  sp = std::min<long>(sp, kMaxBatch);
-  sp = std::min<long>(sp, K / 1024);
-  sp = std::min<long>(sp, (long)(c->skws_floats / ((size_t)M * N)));
-  return sp < 2 ? 1 : (int)sp;
+  if (c->cfg.dtype != IL_BF16) return 1;
+  const long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
+  const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
+  const long cap = std::min<long>(kMaxBatch, (long)(c->skws_floats / ((size_t)M * N)));
+  auto reduce_us = [&](long sp) { return sp < 2 ? 0.0 : 6.0 + (double)(sp + 1) * M * N * 4.0 / 3.0e6; };
+  const double steps = K / 64.0;
+  long sp128 = 1;
+  if (t128 < 200) sp128 = std::max<long>(1, std::min<long>({512 / t128, cap, (long)(K / 1024)}));
+  const double per128 = t128 * sp128 > 256 ? 0.96 : 0.6;  // one workgroup per CU: deeper ring, faster steps
+  const double cost128 = (double)((t128 * sp128 + 511) / 512) * (steps / sp128) * per128 + reduce_us(sp128);
+  long sp256 = std::max<long>(1, std::min<long>({(256 + t256 / 2) / t256, cap, (long)(K / 2048)}));
+  if (t256 * sp256 < 160) return (int)sp128;  // the large tile would not be chosen
+  const double cost256 = (double)((t256 * sp256 + 255) / 256) * (steps / sp256) * 1.6 + reduce_us(sp256);
+  return (int)(cost256 < cost128 ? sp256 : sp128);
 }
 
 int attention_fwd(il_ctx *c, const void *qkv, void *o, float *lse) {
