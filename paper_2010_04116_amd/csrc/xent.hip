@@ -48,12 +48,15 @@ __global__ __launch_bounds__(256) void xent_rows_kernel(T *z, const int32_t *__r
   }
 }
 
-// bf16 rows up to 512*8*J columns: the whole row stays in registers (16-byte vectors strided
-// over 512 threads), so the logits tile is read once and written once.
-template <int J>
-__global__ __launch_bounds__(512) void xent_rows_reg_kernel(bf16_t *z, const int32_t *__restrict__ targets, int V,
+// bf16 rows up to NT*8*J columns: the whole row stays in registers (16-byte vectors strided
+// over the NT threads of the workgroup), so the logits tile is read once and written once.
+// The exponentials go straight to the hardware instruction: every argument is <= 0 up to
+// rounding, and a result below 2^-126 may flush to zero.
+template <int J, int NT>
+__global__ __launch_bounds__(NT) void xent_rows_reg_kernel(bf16_t *z, const int32_t *__restrict__ targets, int V,
                                                             float inv_n, float *__restrict__ rowloss) {
-  __shared__ float red[8];
+  constexpr int NW = NT / 64;
+  __shared__ float red[NW];
   const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   bf16_t *zr = z + (size_t)row * V;
   const int nvec = V >> 3;
@@ -63,7 +66,7 @@ __global__ __launch_bounds__(512) void xent_rows_reg_kernel(bf16_t *z, const int
   float mx = -INFINITY;
 #pragma unroll
   for (int j = 0; j < J; ++j) {
-    const int v = tid + 512 * j;
+    const int v = tid + NT * j;
     if (v < nvec) {
       q[j] = *reinterpret_cast<const uint4 *>(zr + v * 8);
       const uint32_t u[4] = {q[j].x, q[j].y, q[j].z, q[j].w};
@@ -79,39 +82,41 @@ __global__ __launch_bounds__(512) void xent_rows_reg_kernel(bf16_t *z, const int
   __syncthreads();
   mx = red[0];
 #pragma unroll
-  for (int i = 1; i < 8; ++i) mx = fmaxf(mx, red[i]);
+  for (int i = 1; i < NW; ++i) mx = fmaxf(mx, red[i]);
   __syncthreads();
   const float mx2 = mx * 1.4426950408889634f;
   float se = 0.f;
 #pragma unroll
   for (int j = 0; j < J; ++j) {
-    const int v = tid + 512 * j;
+    const int v = tid + NT * j;
     if (v < nvec) {
       const uint32_t u[4] = {q[j].x, q[j].y, q[j].z, q[j].w};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        se += exp2f(bf16_to_f32((bf16_t)(u[e] & 0xFFFF)) * 1.4426950408889634f - mx2);
-        se += exp2f(bf16_to_f32((bf16_t)(u[e] >> 16)) * 1.4426950408889634f - mx2);
+        se += __builtin_amdgcn_exp2f(bf16_to_f32((bf16_t)(u[e] & 0xFFFF)) * 1.4426950408889634f - mx2);
+        se += __builtin_amdgcn_exp2f(bf16_to_f32((bf16_t)(u[e] >> 16)) * 1.4426950408889634f - mx2);
       }
     }
   }
   se = wave_sum(se);
   if (lane == 0) red[wave] = se;
   __syncthreads();
-  se = ((red[0] + red[1]) + (red[2] + red[3])) + ((red[4] + red[5]) + (red[6] + red[7]));
+  se = 0.f;
+#pragma unroll
+  for (int i = 0; i < NW; i += 4) se += (red[i] + red[i + 1]) + (red[i + 2] + red[i + 3]);
   const float lse = mx + __logf(se);
   const float lse2 = lse * 1.4426950408889634f;
   if (tid == 0) rowloss[row] = lse - ztgt;
 #pragma unroll
   for (int j = 0; j < J; ++j) {
-    const int v = tid + 512 * j;
+    const int v = tid + NT * j;
     if (v < nvec) {
       const uint32_t u[4] = {q[j].x, q[j].y, q[j].z, q[j].w};
       float p[8];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        p[2 * e] = exp2f(bf16_to_f32((bf16_t)(u[e] & 0xFFFF)) * 1.4426950408889634f - lse2);
-        p[2 * e + 1] = exp2f(bf16_to_f32((bf16_t)(u[e] >> 16)) * 1.4426950408889634f - lse2);
+        p[2 * e] = __builtin_amdgcn_exp2f(bf16_to_f32((bf16_t)(u[e] & 0xFFFF)) * 1.4426950408889634f - lse2);
+        p[2 * e + 1] = __builtin_amdgcn_exp2f(bf16_to_f32((bf16_t)(u[e] >> 16)) * 1.4426950408889634f - lse2);
       }
       const int c0 = v * 8;
       if (tgt >= c0 && tgt < c0 + 8) {
@@ -138,9 +143,11 @@ hipError_t xent_rows(int dtype, void *z, const int32_t *targets, int rows, int V
     hipLaunchKernelGGL(xent_rows_kernel<float>, dim3(rows), dim3(256), 0, s, (float *)z, targets, V, inv_n,
                        rowloss);
   else if ((V & 7) == 0 && V <= 512 * 8 * 8)
-    hipLaunchKernelGGL(xent_rows_reg_kernel<8>, dim3(rows), dim3(512), 0, s, (bf16_t *)z, targets, V, inv_n, rowloss);
-  else if ((V & 7) == 0 && V <= 512 * 8 * 16)
-    hipLaunchKernelGGL(xent_rows_reg_kernel<16>, dim3(rows), dim3(512), 0, s, (bf16_t *)z, targets, V, inv_n, rowloss);
+    hipLaunchKernelGGL((xent_rows_reg_kernel<8, 512>), dim3(rows), dim3(512), 0, s, (bf16_t *)z, targets, V, inv_n,
+                       rowloss);
+  else if ((V & 7) == 0 && V <= 1024 * 8 * 8)  // wider rows: twice the threads rather than twice the registers
+    hipLaunchKernelGGL((xent_rows_reg_kernel<8, 1024>), dim3(rows), dim3(1024), 0, s, (bf16_t *)z, targets, V, inv_n,
+                       rowloss);
   else
     hipLaunchKernelGGL(xent_rows_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, (bf16_t *)z, targets, V, inv_n,
                        rowloss);
