@@ -187,6 +187,13 @@ struct il_ctx {
   int bparity = 0;
   hipEvent_t ev_blk_ready[2] = {nullptr, nullptr}, ev_blk_done[2] = {nullptr, nullptr};
   char blk_pending[2] = {0, 0};
+  // bf16: the stream sums / first-stage column sums of a block (two launches) also run on the side
+  // stream; Gb_alt is the second home of the bf16 gradient stream that makes this possible
+  char *Gb_alt = nullptr;
+  hipEvent_t ev_fl_ready[2] = {nullptr, nullptr}, ev_fl_done[2] = {nullptr, nullptr};
+  char fl_pending[2] = {0, 0};
+  bool flush_async = false;
+  int flush_idx = 0;
   SumColsumJobs pending; float *pending_out[kMaxSumColsumJobs]; int pending_acc[kMaxSumColsumJobs];
   double pending_bytes = 0;
   char *xb, *Z; float *rowloss, *dxh;
@@ -261,6 +268,7 @@ size_t layout_workspace(il_ctx *c, void *base) {
   const size_t ns = c->plan.nslots + (c->Lh ? 1 : 0), S = (size_t)std::max(c->plan.maxcnt, 1) * N;
   c->G = (float *)cv.take(ns * N * d * 4);
   c->Gb = (c->eb == 4) ? (char *)c->G : (char *)cv.take(ns * N * d * eb);
+  c->Gb_alt = (c->eb == 4) ? nullptr : (char *)cv.take(ns * N * d * eb);
   c->DU = (char *)cv.take(S * m * eb);
   c->DH = (char *)cv.take(S * d * eb);
   c->DQKV = (char *)cv.take(S * 3 * d * eb);
@@ -382,6 +390,8 @@ int ensure_side(il_ctx *c) {
   for (int p = 0; p < 2; ++p) {
     IL_TRY(hipEventCreateWithFlags(&c->ev_blk_ready[p], hipEventDisableTiming));
     IL_TRY(hipEventCreateWithFlags(&c->ev_blk_done[p], hipEventDisableTiming));
+    IL_TRY(hipEventCreateWithFlags(&c->ev_fl_ready[p], hipEventDisableTiming));
+    IL_TRY(hipEventCreateWithFlags(&c->ev_fl_done[p], hipEventDisableTiming));
   }
   return IL_OK;
 }
@@ -393,6 +403,7 @@ int join_block_tails(il_ctx *c) {
       IL_TRY(hipStreamWaitEvent(c->main_stream, c->ev_blk_done[p], 0));
       c->blk_pending[p] = 0;
     }
+  c->fl_pending[0] = c->fl_pending[1] = 0;  // (the side stream is in order: the tails came after them)
   return IL_OK;
 }
 
@@ -402,7 +413,16 @@ int join_block_tails(il_ctx *c) {
 int flush_colsums(il_ctx *c) {
   if (c->pending.count == 0) return IL_OK;
   int nblk = 0;
-  {
+  if (c->flush_async) {
+    const int which = c->flush_idx++ & 1;  // first or second launch of this block
+    // On the side stream, after what the caller's stream has produced so far.  The caller's stream
+    // waits for ev_fl_done[which] before it next overwrites an operand (block_backward).
+    IL_TRY(hipEventRecord(c->ev_fl_ready[which], c->main_stream));
+    IL_TRY(hipStreamWaitEvent(c->side, c->ev_fl_ready[which], 0));
+    IL_TRY(sum_colsum_multi(c->cfg.dtype, c->pending, &nblk, c->side));
+    IL_TRY(hipEventRecord(c->ev_fl_done[which], c->side));
+    c->fl_pending[which] = 1;
+  } else {
     Scope sc(c, KC_COLSUM, 0, c->pending_bytes);
     IL_TRY(sum_colsum_multi(c->cfg.dtype, c->pending, &nblk, c->stream));
   }
@@ -564,21 +584,38 @@ int block_backward(il_ctx *c, const Run &cp, const BlockOff &b, const BlockSave 
     for (int i = 0; i < 4; ++i) c->YS[i] = c->YS2[par][i];
     for (int i = 0; i < 6; ++i) c->partials[i] = c->partials2[par][i];
   }
+  // bf16: the two stream-sum launches go to the side stream as well.  LayerNorm 2's backward then
+  // writes the bf16 stream to its second home (the first is still being read there) and LayerNorm 1's
+  // writes it back; each waits for the side-stream launch that last read what it overwrites (Gb_alt
+  // and DQKV: the previous block's second launch; Gb and DU: this block's first).
+  c->flush_async = async_tail && c->eb == 2;
+  c->flush_idx = 0;
+  char *Gb2 = c->flush_async ? c->Gb_alt + (size_t)cp.s0 * N * d * c->eb : Gb;
+  auto wait_flush = [&](int which) -> int {
+    if (c->flush_async && c->fl_pending[which]) {
+      IL_TRY(hipStreamWaitEvent(c->main_stream, c->ev_fl_done[which], 0));
+      c->fl_pending[which] = 0;
+    }
+    return IL_OK;
+  };
   // MLP
   if ((rc = linear_dgrad(c, Gb, b.w_fc2, S, m, d, EPI_GELU_BWD, c->DU, s.u, N))) return rc;
   if ((rc = linear_wgrad(c, cp, s.gl, Gb, m, d, b.w_fc2, b.b_fc2, 0, true, wg, &nw))) return rc;
   if ((rc = linear_wgrad(c, cp, s.h2, c->DU, d, m, b.w_fc1, b.b_fc1, 1, false, wg, &nw))) return rc;
   if ((rc = linear_dgrad(c, c->DU, b.w_fc1, S, d, m, EPI_STORE, c->DH, nullptr, 0))) return rc;
   if ((rc = flush_colsums(c))) return rc;  // the stream is about to change
-  if ((rc = ln_bwd(c, cp, c->DH, s.a, s.st2, b.ln2_g, G, Gb, 4))) return rc;
+  if ((rc = wait_flush(1))) return rc;
+  if ((rc = ln_bwd(c, cp, c->DH, s.a, s.st2, b.ln2_g, G, Gb2, 4))) return rc;
   // attention
-  if ((rc = linear_wgrad(c, cp, s.o, Gb, d, d, b.w_o, b.b_o, 2, true, wg, &nw))) return rc;
-  if ((rc = linear_dgrad(c, Gb, b.w_o, S, d, d, EPI_STORE, c->DH, nullptr, 0))) return rc;
+  if ((rc = linear_wgrad(c, cp, s.o, Gb2, d, d, b.w_o, b.b_o, 2, true, wg, &nw))) return rc;
+  if ((rc = linear_dgrad(c, Gb2, b.w_o, S, d, d, EPI_STORE, c->DH, nullptr, 0))) return rc;
   if ((rc = attention_bwd(c, s, c->DH, cp.cnt, c->DQKV))) return rc;
   if ((rc = linear_wgrad(c, cp, s.h1, c->DQKV, d, 3 * d, b.w_qkv, b.b_qkv, 3, false, wg, &nw))) return rc;
   if ((rc = linear_dgrad(c, c->DQKV, b.w_qkv, S, d, 3 * d, EPI_STORE, c->DH, nullptr, 0))) return rc;
   if ((rc = flush_colsums(c))) return rc;
+  if ((rc = wait_flush(0))) return rc;
   if ((rc = ln_bwd(c, cp, c->DH, s.xs, s.st1, b.ln1_g, G, Gb, 5))) return rc;
+  c->flush_async = false;
   // The block's tail - second stage of the six column reductions (four bias gradients, two LayerNorm
   // gain/bias pairs) and the four weight gradients in one launch - depends on nothing later and nothing
   // later depends on it: it runs on the side stream, concurrently with the next block's backward.
@@ -952,6 +989,8 @@ int il_free(il_ctx *c) {
   for (int p = 0; p < 2; ++p) {
     if (c->ev_blk_ready[p]) hipEventDestroy(c->ev_blk_ready[p]);
     if (c->ev_blk_done[p]) hipEventDestroy(c->ev_blk_done[p]);
+    if (c->ev_fl_ready[p]) hipEventDestroy(c->ev_fl_ready[p]);
+    if (c->ev_fl_done[p]) hipEventDestroy(c->ev_fl_done[p]);
   }
   if (c->side) hipStreamDestroy(c->side);
   delete c;
