@@ -25,6 +25,8 @@
 
 #include "common.h"
 #include "lds_dma.h"
+#include <type_traits>
+#include <utility>
 
 namespace il {
 namespace {
@@ -183,6 +185,21 @@ struct DmaTile {
       dma16(rs, base + i * (NT * 16), ok ? voff[i] + adv : kOob);
     }
   }
+  // K-contiguous tiles with a 64-deep K step: the swizzled address of fragment (row block i, k
+  // slice ks) differs from that of (0, 0) in bits 5-6 only, by an exclusive-or with a constant
+  // (32 rows toggle bit 2 of g, a k slice adds 2 to the chunk index).  One lane-dependent base per
+  // operand plus a constant per read costs no registers for precomputed addresses, which the
+  // multiply loop of the large tile needs for its accumulators.
+  static constexpr bool XOR_FORM = !KMAJOR && BKT == 64;
+  __device__ static inline uint32_t lane_base(uint32_t lds_addr, int rbase0, int lane) {
+    const int row = rbase0 + (lane & 31);
+    return lds_addr + row * RB + ((((lane >> 5) ^ g(row)) & 7) << 4);
+  }
+  __device__ static inline bf16x8 frag_x(uint32_t base, int i, int ks) {
+    typedef __attribute__((address_space(3))) const bf16x8 *lds_frag;
+    const uint32_t a = (base ^ (uint32_t)(((2 * ks) ^ (4 * (i & 1))) << 4)) + i * 32 * RB;
+    return *reinterpret_cast<lds_frag>((uintptr_t)a);
+  }
   // 32 x 16 MFMA fragment of rows [rbase, rbase+32), k slice ks of the staged K step
   __device__ static inline bf16x8 frag(const char *lds, int rbase, int ks, int lane) {
     if constexpr (!KMAJOR) {
@@ -203,6 +220,16 @@ struct DmaTile {
   }
 };
 
+// f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{})
+template <class F, int... I>
+__device__ inline void static_for_impl(F &&f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ inline void static_for(F &&f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 struct GemmBatch {
   int count;
   int tile_end[kMaxBatch];  // exclusive prefix of tile counts
@@ -216,9 +243,9 @@ struct GemmBatch {
 // their LDS queue; without, every wavefront loads its share and then multiplies (the cheaper
 // arrangement when many small workgroups share a CU and cover for each other).
 constexpr int kLoaderWaves = 4;
-template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGE, bool AKM, bool BKM, int EPI, bool LOADERS = false>
+template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGE, bool AKM, bool BKM, int EPI, int LOADERS = 0>
 __global__ __launch_bounds__(64 * (WGM * WGN + (LOADERS ? kLoaderWaves : 0))) void gemm_dma_kernel(GemmBatch batch) {
-  constexpr bool SPEC = LOADERS;
+  constexpr bool SPEC = LOADERS != 0, PIPE = LOADERS == 2;
   constexpr int NC = 64 * WGM * WGN;                // multiplying threads
   constexpr int NL = SPEC ? 64 * kLoaderWaves : NC;  // threads that share the loading of one tile
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
@@ -226,7 +253,7 @@ __global__ __launch_bounds__(64 * (WGM * WGN + (LOADERS ? kLoaderWaves : 0))) vo
   constexpr int ABYTES = BM * BKT * 2, STAGE = (BM + BN) * BKT * 2;
   constexpr int SP = WTN + 4;
   constexpr int EPIB = WGM * WGN * 32 * SP * 4;  // epilogue staging reuses the operand buffers
-  __shared__ __attribute__((aligned(16))) char smem[NSTAGE * STAGE > EPIB ? NSTAGE * STAGE : EPIB];
+  __shared__ __attribute__((aligned(1024))) char smem[NSTAGE * STAGE > EPIB ? NSTAGE * STAGE : EPIB];
 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -274,6 +301,8 @@ __global__ __launch_bounds__(64 * (WGM * WGN + (LOADERS ? kLoaderWaves : 0))) vo
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  const uint32_t xa = TA::lane_base(lds_address(smem), wm * WTM, lane);
+  const uint32_t xb = TB::lane_base(lds_address(smem) + ABYTES, wn * WTN, lane);
   // K steps kt .. kt+NSTAGE-2 are in flight while step kt is multiplied; one barrier per step:
   // it publishes step kt (every loading thread waited for its own loads of it) and retires the
   // buffer of step kt-1, which the loads issued right after it overwrite.
@@ -314,13 +343,51 @@ __global__ __launch_bounds__(64 * (WGM * WGN + (LOADERS ? kLoaderWaves : 0))) vo
     }
     const char *sa = smem + (kt % NSTAGE) * STAGE;
     const char *sb = sa + ABYTES;
+    const uint32_t soff = (uint32_t)(kt % NSTAGE) * STAGE;  // (added before the exclusive-or: no carry into bits 4-6)
+    if constexpr (PIPE) {
+      // Software pipeline over the (k slice, row block) slots of the step: the A fragment of the next
+      // slot and, two slots before a new k slice, its B fragments are requested before the MFMAs of
+      // the current slot, and the scheduler is held to that order (one group of LDS reads, then the
+      // slot's MFMAs), so a read's latency passes under the previous slot's matrix work.
+      constexpr int KS = BKT / 16, ARD = AKM ? 2 : 1, BRD = BKM ? 2 : 1;  // LDS instructions per fragment
+      auto getA = [&](int ks, int i) {
+        return TA::XOR_FORM ? TA::frag_x(xa + soff, i, ks) : TA::frag(sa, wm * WTM + i * 32, ks, lane);
+      };
+      auto getB = [&](int ks, int j) {
+        return TB::XOR_FORM ? TB::frag_x(xb + soff, j, ks) : TB::frag(sb, wn * WTN + j * 32, ks, lane);
+      };
+      bf16x8 aq[2], bq[2][NI];
+#pragma unroll
+      for (int j = 0; j < NI; ++j) bq[0][j] = getB(0, j);
+      aq[0] = getA(0, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, NI * BRD + ARD, 0);
+      static_for<KS * MI>([&](auto slot_c) {
+        constexpr int slot = decltype(slot_c)::value, ks = slot / MI, i = slot % MI;
+        constexpr bool nextA = i + 1 < MI || ks + 1 < KS;
+        constexpr bool nextB = i == (MI >= 2 ? MI - 2 : 0) && ks + 1 < KS;
+        if constexpr (nextA) aq[(slot + 1) & 1] = i + 1 < MI ? getA(ks, i + 1) : getA(ks + 1, 0);
+        if constexpr (nextB) {
+#pragma unroll
+          for (int j = 0; j < NI; ++j) bq[(ks + 1) & 1][j] = getB(ks + 1, j);
+        }
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[slot & 1], bq[ks & 1][j], acc[i][j], 0, 0, 0);
+        constexpr int reads = (nextA ? ARD : 0) + (nextB ? NI * BRD : 0);
+        if constexpr (reads > 0) __builtin_amdgcn_sched_group_barrier(0x100, reads, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, NI, 0);
+      });
+      continue;
+    }
 #pragma unroll
     for (int ks = 0; ks < BKT / 16; ++ks) {
       bf16x8 af[MI], bfr[NI];
 #pragma unroll
-      for (int i = 0; i < MI; ++i) af[i] = TA::frag(sa, wm * WTM + i * 32, ks, lane);
+      for (int i = 0; i < MI; ++i)
+        af[i] = TA::XOR_FORM ? TA::frag_x(xa + soff, i, ks) : TA::frag(sa, wm * WTM + i * 32, ks, lane);
 #pragma unroll
-      for (int j = 0; j < NI; ++j) bfr[j] = TB::frag(sb, wn * WTN + j * 32, ks, lane);
+      for (int j = 0; j < NI; ++j)
+        bfr[j] = TB::XOR_FORM ? TB::frag_x(xb + soff, j, ks) : TB::frag(sb, wn * WTN + j * 32, ks, lane);
 #pragma unroll
       for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -334,7 +401,7 @@ __global__ __launch_bounds__(64 * (WGM * WGN + (LOADERS ? kLoaderWaves : 0))) vo
 
 thread_local const KernelTimer *tl_timer = nullptr;  // armed by gemm_time_next()
 
-template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGE, bool AKM, bool BKM, int EPI, bool LOADERS = false>
+template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGE, bool AKM, bool BKM, int EPI, int LOADERS = 0>
 hipError_t launch_dma(GemmBatch &b, hipStream_t s) {
   int tiles = 0;
   for (int i = 0; i < b.count; ++i) {
@@ -362,11 +429,11 @@ hipError_t pick_tile(GemmBatch &b, hipStream_t s) {
     t128 += (long)((b.p[i].M + 127) / 128) * ((b.p[i].N + 127) / 128);
   }
   switch (b.p[0].tile) {
-    case 1: return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI, true>(b, s);
-    case 2: return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI, true>(b, s);
-    case 3: return launch_dma<128, 128, 2, 2, 64, 4, AKM, BKM, EPI, true>(b, s);
+    case 1: return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI, 2>(b, s);
+    case 2: return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI, 2>(b, s);
+    case 3: return launch_dma<128, 128, 2, 2, 64, 4, AKM, BKM, EPI, 2>(b, s);
     case 4: return launch_dma<64, 64, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
-    case 5: return launch_dma<64, 64, 2, 2, 64, 4, AKM, BKM, EPI, true>(b, s);
+    case 5: return launch_dma<64, 64, 2, 2, 64, 4, AKM, BKM, EPI, 2>(b, s);
     default: break;
   }
   // Measured on MI355X.  With enough 256x256 tiles to cover most of the 256 CUs the large tile
@@ -375,10 +442,10 @@ hipError_t pick_tile(GemmBatch &b, hipStream_t s) {
   // each CU gets at most one.  When even those leave CUs idle, 64x64 tiles shorten each workgroup's
   // K loop, which is what bounds such a launch: up to five small workgroups per CU that cover
   // for each other, or - if each CU gets only one - loader wavefronts and four stages again.
-  if (t256 >= 160) return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI, true>(b, s);
-  if (t128 > 256) return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI, true>(b, s);
-  if (t128 >= 208) return launch_dma<128, 128, 2, 2, 64, 4, AKM, BKM, EPI, true>(b, s);
-  if (t64 <= 256) return launch_dma<64, 64, 2, 2, 64, 4, AKM, BKM, EPI, true>(b, s);
+  if (t256 >= 160) return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI, 2>(b, s);
+  if (t128 > 256) return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI, 2>(b, s);
+  if (t128 >= 208) return launch_dma<128, 128, 2, 2, 64, 4, AKM, BKM, EPI, 2>(b, s);
+  if (t64 <= 256) return launch_dma<64, 64, 2, 2, 64, 4, AKM, BKM, EPI, 2>(b, s);
   return launch_dma<64, 64, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
 }
 
