@@ -356,23 +356,30 @@ __global__ __launch_bounds__(64 * (WGM * WGN + (LOADERS ? kLoaderWaves : 0))) vo
       auto getB = [&](int ks, int j) {
         return TB::XOR_FORM ? TB::frag_x(xb + soff, j, ks) : TB::frag(sb, wn * WTN + j * 32, ks, lane);
       };
-      bf16x8 aq[2], bq[2][NI];
+      // D slots ahead: two where the accumulators leave room for a third A fragment, else one
+      constexpr int D = (MI * NI <= 4 && MI >= 2) ? 2 : 1;
+      static_assert(D <= MI || MI == 1, "a k slice's B fragments are requested while the previous slice is in use");
+      bf16x8 aq[D + 1], bq[2][NI];
 #pragma unroll
       for (int j = 0; j < NI; ++j) bq[0][j] = getB(0, j);
-      aq[0] = getA(0, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, NI * BRD + ARD, 0);
+#pragma unroll
+      for (int p = 0; p < D; ++p)
+        if (p < KS * MI) aq[p] = getA(p / MI, p % MI);
+      __builtin_amdgcn_sched_group_barrier(0x100, NI * BRD + D * ARD, 0);
       static_for<KS * MI>([&](auto slot_c) {
         constexpr int slot = decltype(slot_c)::value, ks = slot / MI, i = slot % MI;
-        constexpr bool nextA = i + 1 < MI || ks + 1 < KS;
-        constexpr bool nextB = i == (MI >= 2 ? MI - 2 : 0) && ks + 1 < KS;
-        if constexpr (nextA) aq[(slot + 1) & 1] = i + 1 < MI ? getA(ks, i + 1) : getA(ks + 1, 0);
+        constexpr int ahead = slot + D;
+        constexpr bool nextA = ahead < KS * MI;
+        constexpr bool nextB = nextA && ahead % MI == 0;
+        if constexpr (nextA) aq[ahead % (D + 1)] = getA(ahead / MI, ahead % MI);
         if constexpr (nextB) {
 #pragma unroll
-          for (int j = 0; j < NI; ++j) bq[(ks + 1) & 1][j] = getB(ks + 1, j);
+          for (int j = 0; j < NI; ++j) bq[(ahead / MI) & 1][j] = getB(ahead / MI, j);
         }
 #pragma unroll
         for (int j = 0; j < NI; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[slot & 1], bq[ks & 1][j], acc[i][j], 0, 0, 0);
+          acc[i][j] =
+              __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[slot % (D + 1)], bq[ks & 1][j], acc[i][j], 0, 0, 0);
         constexpr int reads = (nextA ? ARD : 0) + (nextB ? NI * BRD : 0);
         if constexpr (reads > 0) __builtin_amdgcn_sched_group_barrier(0x100, reads, 0);
         __builtin_amdgcn_sched_group_barrier(0x008, NI, 0);
