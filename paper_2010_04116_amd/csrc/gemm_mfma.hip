@@ -443,16 +443,18 @@ hipError_t pick_tile(GemmBatch &b, hipStream_t s) {
     case 5: return launch_dma<64, 64, 2, 2, 64, 4, AKM, BKM, EPI, 2>(b, s);
     default: break;
   }
-  // Measured on MI355X.  With enough 256x256 tiles to cover most of the 256 CUs the large tile
-  // wins (fewest operand bytes per flop).  Below that the 128x128 tile: two workgroups per CU with
-  // two stages when there are more tiles than CUs, one workgroup with four stages in flight when
-  // each CU gets at most one.  When even those leave CUs idle, 64x64 tiles shorten each workgroup's
-  // K loop, which is what bounds such a launch: up to five small workgroups per CU that cover
-  // for each other, or - if each CU gets only one - loader wavefronts and four stages again.
+  // Measured on MI355X, with operands that are not already in cache (inside a training step a
+  // weight was last used a step ago).  With enough 256x256 tiles to cover most of the 256 CUs the
+  // large tile wins (fewest operand bytes per flop).  Below that the 128x128 tile: two workgroups per
+  // CU with two stages when there are more tiles than CUs, one workgroup with four stages in flight
+  // when each CU gets at most one.  When even those leave CUs idle, 64x64 tiles shorten each
+  // workgroup's K loop, which is what bounds such a launch: loader wavefronts and four stages while at
+  // most two workgroups land on a CU (the deeper ring covers the trip to HBM), beyond that up to five
+  // plain small workgroups per CU that cover for each other.
   if (t256 >= 160) return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI, 2>(b, s);
   if (t128 > 256) return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI, 2>(b, s);
-  if (t128 >= 208) return launch_dma<128, 128, 2, 2, 64, 4, AKM, BKM, EPI, 2>(b, s);
-  if (t64 <= 256) return launch_dma<64, 64, 2, 2, 64, 4, AKM, BKM, EPI, 2>(b, s);
+  if (t128 >= 192) return launch_dma<128, 128, 2, 2, 64, 4, AKM, BKM, EPI, 2>(b, s);
+  if (t64 <= 512) return launch_dma<64, 64, 2, 2, 64, 4, AKM, BKM, EPI, 2>(b, s);
   return launch_dma<64, 64, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
 }
 
