@@ -242,6 +242,8 @@ struct GemmBatch {
 // nothing but load, NSTAGE-1 tiles ahead, and the multiplying wavefronts never have a load in
 // their LDS queue; without, every wavefront loads its share and then multiplies (the cheaper
 // arrangement when many small workgroups share a CU and cover for each other).
+// LOADERS: 0 = every wavefront loads; 1 = loader wavefronts, multiply loop as the compiler
+// schedules it; 2 = loader wavefronts and the hand-pipelined multiply loop (what the library uses).
 constexpr int kLoaderWaves = 4;
 template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGE, bool AKM, bool BKM, int EPI, int LOADERS = 0>
 __global__ __launch_bounds__(64 * (WGM * WGN + (LOADERS ? kLoaderWaves : 0))) void gemm_dma_kernel(GemmBatch batch) {
