@@ -124,10 +124,10 @@ def test_seeded_random_shapes_every_tile_choice():
     all three dimensions; tile = 0 lets the library choose, the others force each configuration."""
     rng = np.random.default_rng(20100411)
     dims = [8, 16, 24, 40, 64, 72, 120, 128, 136, 200, 256, 264, 328, 520]
-    for case in range(36):
+    for case in range(45):
         M, N, K = (int(rng.choice(dims)) for _ in range(3))
         akm, bkm, epi = _COMBOS[case % len(_COMBOS)]
-        tile = [0, 1, 2, 3, 4, 5, 0][case % 7]
+        tile = [0, 1, 2, 3, 4, 5, 6, 7, 0][case % 9]
         print("case", case, M, N, K, akm, bkm, epi, "tile", tile, flush=True)
         run_case(M, N, K, akm, bkm, epi, tile, seed=1000 + case, beta=case & 1, scale=0.5 if case & 2 else 1.0)
 
