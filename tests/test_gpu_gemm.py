@@ -104,6 +104,19 @@ def test_multi_tile_shapes(tile):
     run_case(512, 1024, 2048, 1, 1, 6, tile, seed=42)
 
 
+def test_library_choice_at_the_benchmark_shapes():
+    """tile = 0 at output shapes of the benchmark workloads, one per branch of the tile choice
+    (256x256; 128x128 four-stage; 128x256 / 256x128; 128x128 two-stage; 64x64 four-stage; 64x64),
+    with a short K so that the float64 product stays cheap."""
+    run_case(4096, 4096, 192, 0, 1, 2, 0, seed=50)      # 256 tiles of 256x256
+    run_case(4096, 1024, 192, 0, 1, 3, 0, seed=51)      # 256 tiles of 128x128
+    run_case(8192, 1024, 192, 0, 0, 0, 0, seed=52)      # 256 tiles of 128x256
+    run_case(1024, 8192, 192, 1, 1, 6, 0, seed=53)      # 256 tiles of 256x128 (k-major operands)
+    run_case(4096, 1536, 192, 0, 0, 5, 0, seed=54)      # 384 tiles of 128x128
+    run_case(2048, 512, 192, 0, 1, 3, 0, seed=55)       # 256 tiles of 64x64
+    run_case(2048, 1536, 192, 0, 1, 1, 0, seed=56)      # 768 tiles of 64x64
+
+
 def test_unsupported_combinations_are_rejected():
     import torch
     dev = torch.device("cuda:0")
