@@ -49,6 +49,57 @@ __device__ inline u32x4 pack8(const float (&f)[8]) {
   return v;
 }
 
+// One row's eight consecutive output columns: the epilogue operation and the store.
+template <int EPI>
+__device__ inline void emit8(const GemmArgs &g, float4 v0, float4 v1, int grow, int gcol, const float (&bv)[8]) {
+  if (grow >= g.M || gcol >= g.N) return;
+  float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+  const size_t o = (size_t)grow * g.ldc + gcol;
+  if constexpr (EPI == EPI_STORE) {
+    *reinterpret_cast<u32x4 *>((bf16_t *)g.C + o) = pack8(v);
+  } else if constexpr (EPI == EPI_BIAS) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] += bv[e];
+    *reinterpret_cast<u32x4 *>((bf16_t *)g.C + o) = pack8(v);
+  } else if constexpr (EPI == EPI_BIAS_GELU) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] += bv[e];
+    const u32x4 u = pack8(v);
+    *reinterpret_cast<u32x4 *>((bf16_t *)g.C + o) = u;
+    unpack8(u, v);  // the activation is taken of the stored (rounded) pre-activation
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
+    *reinterpret_cast<u32x4 *>((bf16_t *)g.C2 + o) = pack8(v);
+  } else if constexpr (EPI == EPI_BIAS_RES) {
+    const float4 r0 = *reinterpret_cast<const float4 *>(g.res + o);
+    const float4 r1 = *reinterpret_cast<const float4 *>(g.res + o + 4);
+    float4 o0 = {v[0] + bv[0] + r0.x, v[1] + bv[1] + r0.y, v[2] + bv[2] + r0.z, v[3] + bv[3] + r0.w};
+    float4 o1 = {v[4] + bv[4] + r1.x, v[5] + bv[5] + r1.y, v[6] + bv[6] + r1.z, v[7] + bv[7] + r1.w};
+    *reinterpret_cast<float4 *>((float *)g.C + o) = o0;
+    *reinterpret_cast<float4 *>((float *)g.C + o + 4) = o1;
+  } else if constexpr (EPI == EPI_GELU_BWD) {
+    float u[8];
+    unpack8(*reinterpret_cast<const u32x4 *>((const bf16_t *)g.aux + (size_t)(grow % g.aux_wrap) * g.ldc + gcol), u);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(u[e]);
+    *reinterpret_cast<u32x4 *>((bf16_t *)g.C + o) = pack8(v);
+  } else if constexpr (EPI == EPI_STORE_F32) {
+    *reinterpret_cast<float4 *>((float *)g.C + o) = v0;
+    *reinterpret_cast<float4 *>((float *)g.C + o + 4) = v1;
+  } else {  // EPI_WGRAD
+    float *c = (float *)g.C + o;
+    float4 o0 = {g.scale * v[0], g.scale * v[1], g.scale * v[2], g.scale * v[3]};
+    float4 o1 = {g.scale * v[4], g.scale * v[5], g.scale * v[6], g.scale * v[7]};
+    if (g.beta) {
+      const float4 c0 = *reinterpret_cast<const float4 *>(c), c1 = *reinterpret_cast<const float4 *>(c + 4);
+      o0.x += c0.x; o0.y += c0.y; o0.z += c0.z; o0.w += c0.w;
+      o1.x += c1.x; o1.y += c1.y; o1.z += c1.z; o1.w += c1.w;
+    }
+    *reinterpret_cast<float4 *>(c) = o0;
+    *reinterpret_cast<float4 *>(c + 4) = o1;
+  }
+}
+
 // ---- epilogue shared by both kernels ------------------------------------------------------
 template <int BM, int BN, int WGM, int WGN, int EPI, int MI, int NI>
 __device__ inline void epilogue(const GemmArgs &g, floatx16 (&acc)[MI][NI], char *smem, int m0, int n0, int wave,
@@ -82,52 +133,7 @@ __device__ inline void epilogue(const GemmArgs &g, floatx16 (&acc)[MI][NI], char
       const int grow = m0 + wm * WTM + i * 32 + row_l;
       const float4 v0 = *reinterpret_cast<const float4 *>(stg + row_l * SP + col_l);
       const float4 v1 = *reinterpret_cast<const float4 *>(stg + row_l * SP + col_l + 4);
-      if (grow >= g.M || gcol >= g.N) continue;
-      float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
-      const size_t o = (size_t)grow * g.ldc + gcol;
-      if constexpr (EPI == EPI_STORE) {
-        *reinterpret_cast<u32x4 *>((bf16_t *)g.C + o) = pack8(v);
-      } else if constexpr (EPI == EPI_BIAS) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] += bv[e];
-        *reinterpret_cast<u32x4 *>((bf16_t *)g.C + o) = pack8(v);
-      } else if constexpr (EPI == EPI_BIAS_GELU) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] += bv[e];
-        const u32x4 u = pack8(v);
-        *reinterpret_cast<u32x4 *>((bf16_t *)g.C + o) = u;
-        unpack8(u, v);  // the activation is taken of the stored (rounded) pre-activation
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = gelu_f(v[e]);
-        *reinterpret_cast<u32x4 *>((bf16_t *)g.C2 + o) = pack8(v);
-      } else if constexpr (EPI == EPI_BIAS_RES) {
-        const float4 r0 = *reinterpret_cast<const float4 *>(g.res + o);
-        const float4 r1 = *reinterpret_cast<const float4 *>(g.res + o + 4);
-        float4 o0 = {v[0] + bv[0] + r0.x, v[1] + bv[1] + r0.y, v[2] + bv[2] + r0.z, v[3] + bv[3] + r0.w};
-        float4 o1 = {v[4] + bv[4] + r1.x, v[5] + bv[5] + r1.y, v[6] + bv[6] + r1.z, v[7] + bv[7] + r1.w};
-        *reinterpret_cast<float4 *>((float *)g.C + o) = o0;
-        *reinterpret_cast<float4 *>((float *)g.C + o + 4) = o1;
-      } else if constexpr (EPI == EPI_GELU_BWD) {
-        float u[8];
-        unpack8(*reinterpret_cast<const u32x4 *>((const bf16_t *)g.aux + (size_t)(grow % g.aux_wrap) * g.ldc + gcol), u);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] *= gelu_grad_f(u[e]);
-        *reinterpret_cast<u32x4 *>((bf16_t *)g.C + o) = pack8(v);
-      } else if constexpr (EPI == EPI_STORE_F32) {
-        *reinterpret_cast<float4 *>((float *)g.C + o) = v0;
-        *reinterpret_cast<float4 *>((float *)g.C + o + 4) = v1;
-      } else {  // EPI_WGRAD
-        float *c = (float *)g.C + o;
-        float4 o0 = {g.scale * v[0], g.scale * v[1], g.scale * v[2], g.scale * v[3]};
-        float4 o1 = {g.scale * v[4], g.scale * v[5], g.scale * v[6], g.scale * v[7]};
-        if (g.beta) {
-          const float4 c0 = *reinterpret_cast<const float4 *>(c), c1 = *reinterpret_cast<const float4 *>(c + 4);
-          o0.x += c0.x; o0.y += c0.y; o0.z += c0.z; o0.w += c0.w;
-          o1.x += c1.x; o1.y += c1.y; o1.z += c1.z; o1.w += c1.w;
-        }
-        *reinterpret_cast<float4 *>(c) = o0;
-        *reinterpret_cast<float4 *>(c + 4) = o1;
-      }
+      emit8<EPI>(g, v0, v1, grow, gcol, bv);
     }
     __syncthreads();
   }
@@ -408,6 +414,177 @@ __global__ __launch_bounds__(64 * (WGM * WGN + (LOADERS ? kLoaderWaves : 0))) vo
   epilogue<BM, BN, WGM, WGN, EPI>(g, acc, smem, m0, n0, wave, lane);
 }
 
+// ------------------------------------------------------------------------------------------
+// Persistent variant of the two-stage loader kernel for launches of several rounds: one workgroup
+// per CU walks over tiles blockIdx.x, blockIdx.x + gridDim.x, ...  The K steps of successive tiles
+// form one sequence through the two-stage ring, so the loader wavefronts fetch the first step of the
+// next tile while the multiplying wavefronts are in the epilogue of the current one, and no workgroup
+// is launched per tile.  The epilogue stages 8-row strips in LDS of its own behind the ring (the ring
+// is busy) and needs no workgroup barrier: a strip is private to its wavefront, whose LDS
+// operations complete in order.
+template <int BM, int BN, int WGM, int WGN, int BKT, bool AKM, bool BKM, int EPI>
+__global__ __launch_bounds__(64 * (WGM * WGN + kLoaderWaves)) void gemm_persist_kernel(GemmBatch batch) {
+  constexpr int NSTAGE = 2;
+  constexpr int NC = 64 * WGM * WGN, NL = 64 * kLoaderWaves;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int MI = WTM / 32, NI = WTN / 32;
+  constexpr int ABYTES = BM * BKT * 2, STAGE = (BM + BN) * BKT * 2;
+  constexpr int SP = WTN + 4;
+  constexpr int STRIP = 8 * SP * 4;  // one wavefront's 8-row strip
+  __shared__ __attribute__((aligned(1024))) char smem[NSTAGE * STAGE + WGM * WGN * STRIP];
+
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int wm = wave / WGN, wn = wave % WGN;
+  const bool loader = wave >= WGM * WGN;
+  const int lwave = wave % (NL / 64);
+  const int ntiles = batch.tile_end[batch.count - 1];
+  typedef DmaTile<BM, BKT, AKM, NL> TA;
+  typedef DmaTile<BN, BKT, BKM, NL> TB;
+
+  // tile id -> problem, tile origin, K range (uniform)
+  struct Where { int prob, m0, n0, kb0, ke, nk; };
+  auto locate = [&](int tl) {
+    Where w;
+    w.prob = 0;
+    int tile0 = 0;
+    for (int i = 0; i < batch.count - 1; ++i)
+      if (tl >= batch.tile_end[i]) { w.prob = i + 1; tile0 = batch.tile_end[i]; }
+    const GemmArgs &g = batch.p[w.prob];
+    const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    const int total = tiles_m * tiles_n;
+    int pid = tl - tile0;
+    if ((total & 7) == 0) pid = (pid & 7) * (total >> 3) + (pid >> 3);
+    constexpr int GM = 8;
+    const int per_group = GM * tiles_n;
+    const int group = pid / per_group, first_m = group * GM;
+    const int gsize = min(tiles_m - first_m, GM);
+    w.m0 = (first_m + (pid % per_group) % gsize) * BM;
+    w.n0 = ((pid % per_group) / gsize) * BN;
+    w.kb0 = g.k_end > 0 ? g.k_begin : 0;
+    w.ke = g.k_end > 0 ? g.k_end : g.K;
+    w.nk = (w.ke - w.kb0 + BKT - 1) / BKT;
+    return w;
+  };
+
+  if (loader) {
+    // Step s of the sequence goes to ring slot s & 1; it is issued right after the barrier of step
+    // s - 1 (which retires slot s & 1) and awaited before the barrier of step s.
+    int seq = 0;
+    TA la;
+    TB lb;
+    BufRsrc ra, rb;
+    Where w = locate(blockIdx.x);
+    auto setup = [&]() {
+      const GemmArgs &g = batch.p[w.prob];
+      ra = make_rsrc(g.A, g.a_bytes);
+      rb = make_rsrc(g.B, g.b_bytes);
+      la.init(w.m0, g.M, g.lda, t % NL);
+      lb.init(w.n0, g.N, g.ldb, t % NL);
+    };
+    auto issue = [&](int kt, int slot) {
+      char *st = smem + slot * STAGE;
+      la.issue(ra, st, lwave, w.kb0 + kt * BKT, w.ke);
+      lb.issue(rb, st + ABYTES, lwave, w.kb0 + kt * BKT, w.ke);
+    };
+    setup();
+    issue(0, 0);
+    for (int tl = blockIdx.x; tl < ntiles; tl += gridDim.x) {
+      for (int kt = 0; kt < w.nk; ++kt) {
+        wait_vmcnt<0>();
+        __syncthreads();
+        ++seq;
+        if (kt + 1 < w.nk) {
+          issue(kt + 1, seq & 1);
+        } else if (tl + (int)gridDim.x < ntiles) {  // first step of the next tile
+          w = locate(tl + gridDim.x);
+          setup();
+          issue(0, seq & 1);
+          break;  // (w now describes the next tile)
+        }
+      }
+    }
+    wait_vmcnt<0>();
+    return;
+  }
+
+  const uint32_t xa = TA::lane_base(lds_address(smem), wm * WTM, lane);
+  const uint32_t xb = TB::lane_base(lds_address(smem) + ABYTES, wn * WTN, lane);
+  float *stg = reinterpret_cast<float *>(smem + NSTAGE * STAGE) + wave * (8 * SP);
+  constexpr int LPR = WTN / 8;
+  static_assert(LPR == 8, "one 8-row strip per pass");
+  const int hh = lane >> 5, lq = lane & 31;
+  const int col_l = (lane % LPR) * 8, row_in = lane / LPR;
+  int seq = 0;
+  for (int tl = blockIdx.x; tl < ntiles; tl += gridDim.x) {
+    const Where w = locate(tl);
+    const GemmArgs &g = batch.p[w.prob];
+    floatx16 acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    for (int kt = 0; kt < w.nk; ++kt) {
+      __syncthreads();
+      const uint32_t soff = (uint32_t)(seq & 1) * STAGE;
+      const char *sa = smem + soff, *sb = sa + ABYTES;
+      ++seq;
+      constexpr int KS = BKT / 16, ARD = AKM ? 2 : 1, BRD = BKM ? 2 : 1;
+      auto getA = [&](int ks, int i) {
+        return TA::XOR_FORM ? TA::frag_x(xa + soff, i, ks) : TA::frag(sa, wm * WTM + i * 32, ks, lane);
+      };
+      auto getB = [&](int ks, int j) {
+        return TB::XOR_FORM ? TB::frag_x(xb + soff, j, ks) : TB::frag(sb, wn * WTN + j * 32, ks, lane);
+      };
+      bf16x8 aq[2], bq[2][NI];
+#pragma unroll
+      for (int j = 0; j < NI; ++j) bq[0][j] = getB(0, j);
+      aq[0] = getA(0, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, NI * BRD + ARD, 0);
+      static_for<KS * MI>([&](auto slot_c) {
+        constexpr int slot = decltype(slot_c)::value, ks = slot / MI, i = slot % MI;
+        constexpr int ahead = slot + 1;
+        constexpr bool nextA = ahead < KS * MI;
+        constexpr bool nextB = nextA && ahead % MI == 0;
+        if constexpr (nextA) aq[ahead & 1] = getA(ahead / MI, ahead % MI);
+        if constexpr (nextB) {
+#pragma unroll
+          for (int j = 0; j < NI; ++j) bq[(ahead / MI) & 1][j] = getB(ahead / MI, j);
+        }
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[slot & 1], bq[ks & 1][j], acc[i][j], 0, 0, 0);
+        constexpr int reads = (nextA ? ARD : 0) + (nextB ? NI * BRD : 0);
+        if constexpr (reads > 0) __builtin_amdgcn_sched_group_barrier(0x100, reads, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, NI, 0);
+      });
+    }
+    // epilogue: a lane holds column (lane & 31) and rows 8*(r/4) + 4*(lane>>5) + (r&3) of each 32x32
+    // block; strip q of block row i is rows 8q .. 8q+7, i.e. accumulator elements 4q .. 4q+3.
+    const int gcol = w.n0 + wn * WTN + col_l;
+    float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_RES) {
+      if (gcol < g.N) unpack8(*reinterpret_cast<const u32x4 *>((const bf16_t *)g.bias + gcol), bv);
+    }
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) stg[(4 * hh + e) * SP + j * 32 + lq] = acc[i][j][4 * q + e];
+        asm volatile("" ::: "memory");
+        const float4 v0 = *reinterpret_cast<const float4 *>(stg + row_in * SP + col_l);
+        const float4 v1 = *reinterpret_cast<const float4 *>(stg + row_in * SP + col_l + 4);
+        asm volatile("" ::: "memory");
+        emit8<EPI>(g, v0, v1, w.m0 + wm * WTM + i * 32 + 8 * q + row_in, gcol, bv);
+      }
+  }
+}
+
 thread_local const KernelTimer *tl_timer = nullptr;  // armed by gemm_time_next()
 
 template <int BM, int BN, int WGM, int WGN, int BKT, int NSTAGE, bool AKM, bool BKM, int EPI, int LOADERS = 0>
@@ -425,6 +602,25 @@ hipError_t launch_dma(GemmBatch &b, hipStream_t s) {
   } else {
     hipLaunchKernelGGL((gemm_dma_kernel<BM, BN, WGM, WGN, BKT, NSTAGE, AKM, BKM, EPI, LOADERS>), dim3(tiles),
                        dim3(nthreads), 0, s, b);
+  }
+  return hipGetLastError();
+}
+
+template <int BM, int BN, int WGM, int WGN, int BKT, bool AKM, bool BKM, int EPI>
+hipError_t launch_persist(GemmBatch &b, hipStream_t s) {
+  int tiles = 0;
+  for (int i = 0; i < b.count; ++i) {
+    tiles += ((b.p[i].M + BM - 1) / BM) * ((b.p[i].N + BN - 1) / BN);
+    b.tile_end[i] = tiles;
+  }
+  constexpr int nthreads = 64 * (WGM * WGN + kLoaderWaves);
+  const int grid = std::min(tiles, 256);  // one workgroup per CU
+  if (const KernelTimer *t = tl_timer) {
+    tl_timer = nullptr;
+    hipExtLaunchKernelGGL((gemm_persist_kernel<BM, BN, WGM, WGN, BKT, AKM, BKM, EPI>), dim3(grid), dim3(nthreads), 0, s,
+                          t->start, t->stop, 0, b);
+  } else {
+    hipLaunchKernelGGL((gemm_persist_kernel<BM, BN, WGM, WGN, BKT, AKM, BKM, EPI>), dim3(grid), dim3(nthreads), 0, s, b);
   }
   return hipGetLastError();
 }
@@ -447,6 +643,7 @@ hipError_t pick_tile(GemmBatch &b, hipStream_t s) {
     case 5: return launch_dma<64, 64, 2, 2, 64, 4, AKM, BKM, EPI, 2>(b, s);
     case 6: return launch_dma<256, 128, 4, 2, 64, 3, AKM, BKM, EPI, 2>(b, s);
     case 7: return launch_dma<128, 256, 2, 4, 64, 3, AKM, BKM, EPI, 2>(b, s);
+    case 8: return launch_persist<256, 256, 2, 4, 64, AKM, BKM, EPI>(b, s);
     default: break;
   }
   // Measured on MI355X, with operands that are not already in cache (inside a training step a
@@ -457,7 +654,7 @@ hipError_t pick_tile(GemmBatch &b, hipStream_t s) {
   // workgroup's K loop, which is what bounds such a launch: loader wavefronts and four stages while at
   // most two workgroups land on a CU (the deeper ring covers the trip to HBM), beyond that up to five
   // plain small workgroups per CU that cover for each other.
-  if (t256 >= 160) return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI, 2>(b, s);
+  if (t256 >= 160) return launch_persist<256, 256, 2, 4, 64, AKM, BKM, EPI>(b, s);
   if (t128 >= 192 && t128 <= 256) return launch_dma<128, 128, 2, 2, 64, 4, AKM, BKM, EPI, 2>(b, s);
   // about one 256x128 (or 128x256) tile per CU, three stages: as good as the 128x128 tile on cached
   // operands and 15-20 % better on operands from HBM (fewer bytes per flop, deeper ring)

@@ -958,7 +958,7 @@ int il_test_gemm(int32_t dtype, const void *A, const void *B, int32_t M, int32_t
                  int32_t beta, int32_t tile, void *stream) {
   if (!A || !B || !C || M < 1 || N < 1 || K < 1) return IL_E_ARG;
   if (dtype != IL_F32 && dtype != IL_BF16) return IL_E_ARG;
-  if (epi < EPI_STORE || epi > EPI_WGRAD || tile < 0 || tile > 7) return IL_E_ARG;
+  if (epi < EPI_STORE || epi > EPI_WGRAD || tile < 0 || tile > 8) return IL_E_ARG;
   if ((epi == EPI_BIAS || epi == EPI_BIAS_GELU || epi == EPI_BIAS_RES) && !bias) return IL_E_ARG;
   if ((epi == EPI_BIAS_RES && !res) || (epi == EPI_BIAS_GELU && !C2)) return IL_E_ARG;
   if (epi == EPI_GELU_BWD && (!aux || aux_wrap < 1)) return IL_E_ARG;

@@ -7,7 +7,7 @@ import pytest
 from paper_2010_04116_amd import binding as b, synth
 
 pytestmark = pytest.mark.gpu
-TILES = [1, 2, 3, 4, 5, 6, 7]
+TILES = [1, 2, 3, 4, 5, 6, 7, 8]
 
 
 def _bf16(a):
