@@ -100,43 +100,46 @@ __device__ inline void emit8(const GemmArgs &g, float4 v0, float4 v1, int grow, 
   }
 }
 
-// ---- epilogue shared by both kernels ------------------------------------------------------
-template <int BM, int BN, int WGM, int WGN, int EPI, int MI, int NI>
-__device__ inline void epilogue(const GemmArgs &g, floatx16 (&acc)[MI][NI], char *smem, int m0, int n0, int wave,
-                                int lane) {
-  constexpr int WTM = BM / WGM, WTN = BN / WGN;
-  constexpr int SP = WTN + 4;
-  const int wm = wave / WGN, wn = wave % WGN;
-  // ---- epilogue.  A lane holds column (lane & 31) and rows 8*(r/4) + 4*(lane>>5) + (r&3) of
-  // each 32x32 tile; each wavefront passes one 32-row strip at a time through its own LDS
-  // region so that every lane ends up with 8 consecutive columns of one row: 16-byte bf16 /
-  // 32-byte fp32 stores and equally wide reads of bias, residual and pre-activation.
-  float *stg = reinterpret_cast<float *>(smem) + wave * (32 * SP);
-  constexpr int LPR = WTN / 8, RPP = 64 / LPR, PASSES = 32 / RPP;
+// ---- epilogue shared by the kernels ---------------------------------------------------------
+// A lane holds column (lane & 31) and rows 8*(r/4) + 4*(lane>>5) + (r&3) of each 32x32 block.  Each
+// wavefront passes strips of 8 (64-wide wave tile) or 16 rows through an LDS region of its own so
+// that every lane ends up with 8 consecutive columns of one row: 16-byte bf16 / 32-byte fp32 stores
+// and equally wide reads of bias, residual and pre-activation.  No workgroup barrier is involved:
+// the strip is private to the wavefront, whose LDS operations complete in issue order.
+template <int WTN>
+struct EpiStrip {
+  static constexpr int SP = WTN + 4, LPR = WTN / 8, RPP = 64 / LPR, GPS = RPP / 8, NSTRIP = 32 / RPP;
+  static constexpr int FLOATS = RPP * SP;  // per wavefront
+};
+template <int WTN, int EPI, int MI, int NI>
+__device__ inline void epilogue_strips(const GemmArgs &g, floatx16 (&acc)[MI][NI], float *stg, int row0, int col0,
+                                       int lane) {
+  typedef EpiStrip<WTN> E;
+  constexpr int SP = E::SP;
   const int hh = lane >> 5, lq = lane & 31;
-  const int col_l = (lane % LPR) * 8, row_in = lane / LPR;
-  const int gcol = n0 + wn * WTN + col_l;
+  const int col_l = (lane % E::LPR) * 8, row_in = lane / E::LPR;
+  const int gcol = col0 + col_l;
   float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_RES) {
     if (gcol < g.N) unpack8(*reinterpret_cast<const u32x4 *>((const bf16_t *)g.bias + gcol), bv);
   }
 #pragma unroll
-  for (int i = 0; i < MI; ++i) {
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
-    for (int j = 0; j < NI; ++j)
+    for (int p = 0; p < E::NSTRIP; ++p) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) stg[(8 * (r >> 2) + 4 * hh + (r & 3)) * SP + j * 32 + lq] = acc[i][j][r];
-    __syncthreads();
+      for (int j = 0; j < NI; ++j)
 #pragma unroll
-    for (int p = 0; p < PASSES; ++p) {
-      const int row_l = p * RPP + row_in;
-      const int grow = m0 + wm * WTM + i * 32 + row_l;
-      const float4 v0 = *reinterpret_cast<const float4 *>(stg + row_l * SP + col_l);
-      const float4 v1 = *reinterpret_cast<const float4 *>(stg + row_l * SP + col_l + 4);
-      emit8<EPI>(g, v0, v1, grow, gcol, bv);
+        for (int gq = 0; gq < E::GPS; ++gq)
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            stg[(8 * gq + 4 * hh + e) * SP + j * 32 + lq] = acc[i][j][4 * (p * E::GPS + gq) + e];
+      asm volatile("" ::: "memory");
+      const float4 v0 = *reinterpret_cast<const float4 *>(stg + row_in * SP + col_l);
+      const float4 v1 = *reinterpret_cast<const float4 *>(stg + row_in * SP + col_l + 4);
+      asm volatile("" ::: "memory");
+      emit8<EPI>(g, v0, v1, row0 + i * 32 + p * E::RPP + row_in, gcol, bv);
     }
-    __syncthreads();
-  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -259,8 +262,7 @@ __global__ __launch_bounds__(64 * (WGM * WGN + (LOADERS ? kLoaderWaves : 0))) vo
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int MI = WTM / 32, NI = WTN / 32;
   constexpr int ABYTES = BM * BKT * 2, STAGE = (BM + BN) * BKT * 2;
-  constexpr int SP = WTN + 4;
-  constexpr int EPIB = WGM * WGN * 32 * SP * 4;  // epilogue staging reuses the operand buffers
+  constexpr int EPIB = WGM * WGN * EpiStrip<WTN>::FLOATS * 4;  // epilogue staging reuses the operand buffers
   __shared__ __attribute__((aligned(1024))) char smem[NSTAGE * STAGE > EPIB ? NSTAGE * STAGE : EPIB];
 
   const int t = threadIdx.x, lane = t & 63;
@@ -329,12 +331,7 @@ __global__ __launch_bounds__(64 * (WGM * WGN + (LOADERS ? kLoaderWaves : 0))) vo
       __syncthreads();
       if (kt + NSTAGE - 1 < nk) issue(kt + NSTAGE - 1);
     }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < MI; ++i) {
-      __syncthreads();
-      __syncthreads();
-    }
+    __syncthreads();  // (the one barrier between the last multiply and the epilogue's use of the ring)
     return;
   }
 
@@ -410,8 +407,9 @@ __global__ __launch_bounds__(64 * (WGM * WGN + (LOADERS ? kLoaderWaves : 0))) vo
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
     }
   }
-  __syncthreads();
-  epilogue<BM, BN, WGM, WGN, EPI>(g, acc, smem, m0, n0, wave, lane);
+  __syncthreads();  // every wavefront is done with the ring
+  epilogue_strips<WTN, EPI>(g, acc, reinterpret_cast<float *>(smem) + wave * EpiStrip<WTN>::FLOATS, m0 + wm * WTM,
+                            n0 + wn * WTN, lane);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -429,9 +427,7 @@ __global__ __launch_bounds__(64 * (WGM * WGN + kLoaderWaves)) void gemm_persist_
   constexpr int WTM = BM / WGM, WTN = BN / WGN;
   constexpr int MI = WTM / 32, NI = WTN / 32;
   constexpr int ABYTES = BM * BKT * 2, STAGE = (BM + BN) * BKT * 2;
-  constexpr int SP = WTN + 4;
-  constexpr int STRIP = 8 * SP * 4;  // one wavefront's 8-row strip
-  __shared__ __attribute__((aligned(1024))) char smem[NSTAGE * STAGE + WGM * WGN * STRIP];
+  __shared__ __attribute__((aligned(1024))) char smem[NSTAGE * STAGE + WGM * WGN * EpiStrip<WTN>::FLOATS * 4];
 
   const int t = threadIdx.x, lane = t & 63;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
@@ -510,11 +506,7 @@ __global__ __launch_bounds__(64 * (WGM * WGN + kLoaderWaves)) void gemm_persist_
 
   const uint32_t xa = TA::lane_base(lds_address(smem), wm * WTM, lane);
   const uint32_t xb = TB::lane_base(lds_address(smem) + ABYTES, wn * WTN, lane);
-  float *stg = reinterpret_cast<float *>(smem + NSTAGE * STAGE) + wave * (8 * SP);
-  constexpr int LPR = WTN / 8;
-  static_assert(LPR == 8, "one 8-row strip per pass");
-  const int hh = lane >> 5, lq = lane & 31;
-  const int col_l = (lane % LPR) * 8, row_in = lane / LPR;
+  float *stg = reinterpret_cast<float *>(smem + NSTAGE * STAGE) + wave * EpiStrip<WTN>::FLOATS;
   int seq = 0;
   for (int tl = blockIdx.x; tl < ntiles; tl += gridDim.x) {
     const Where w = locate(tl);
@@ -561,27 +553,7 @@ __global__ __launch_bounds__(64 * (WGM * WGN + kLoaderWaves)) void gemm_persist_
         __builtin_amdgcn_sched_group_barrier(0x008, NI, 0);
       });
     }
-    // epilogue: a lane holds column (lane & 31) and rows 8*(r/4) + 4*(lane>>5) + (r&3) of each 32x32
-    // block; strip q of block row i is rows 8q .. 8q+7, i.e. accumulator elements 4q .. 4q+3.
-    const int gcol = w.n0 + wn * WTN + col_l;
-    float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    if constexpr (EPI == EPI_BIAS || EPI == EPI_BIAS_GELU || EPI == EPI_BIAS_RES) {
-      if (gcol < g.N) unpack8(*reinterpret_cast<const u32x4 *>((const bf16_t *)g.bias + gcol), bv);
-    }
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) stg[(4 * hh + e) * SP + j * 32 + lq] = acc[i][j][4 * q + e];
-        asm volatile("" ::: "memory");
-        const float4 v0 = *reinterpret_cast<const float4 *>(stg + row_in * SP + col_l);
-        const float4 v1 = *reinterpret_cast<const float4 *>(stg + row_in * SP + col_l + 4);
-        asm volatile("" ::: "memory");
-        emit8<EPI>(g, v0, v1, w.m0 + wm * WTM + i * 32 + 8 * q + row_in, gcol, bv);
-      }
+    epilogue_strips<WTN, EPI>(g, acc, stg, w.m0 + wm * WTM, w.n0 + wn * WTN, lane);
   }
 }
 
