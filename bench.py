@@ -153,7 +153,7 @@ def measure(w, steps, warmup):
         "mfma_utilisation_pct_of_bf16_peak": 100.0 * flops / (ms * 1e-3) / (PEAK_BF16_TFLOPS * 1e12),
         "algorithmic_tflop_per_step": flops / 1e12,
         "roofline": {"bound": "mfma" if w.dtype == "bf16" else "alu",
-                     "kernel": "gemm_dma_kernel: every GEMM launch of one step (forward, dgrad, wgrad, head)"
+                     "kernel": "gemm_dma_kernel / gemm_persist_kernel: every GEMM launch of one step (forward, dgrad, wgrad, head)"
                      if w.dtype == "bf16" else "gemm_simt_kernel: every GEMM launch of one step",
                      "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
                      "traffic": MEASURED_TRAFFIC.get(f"{w.name}_{w.dtype}_n{w.n}"),
