@@ -207,7 +207,8 @@ int il_profile_read(il_ctx *ctx, int32_t cap, const char **names, int64_t *launc
  * tile: 0 = library's choice, else (bf16 only; "+4" = four wavefronts that only load)
  *       1 = 256x256 / 8+4 wavefronts, 2 = 128x128 / 4+4, two K steps staged, 3 = 128x128 / 4+4, four staged,
  *       4 = 64x64 / 4 wavefronts, 5 = 64x64 / 4+4, four staged, 6 = 256x128 / 8+4, three staged,
- *       7 = 128x256 / 8+4, three staged.
+ *       7 = 128x256 / 8+4, three staged, 8 = 256x256 / 8+4 as a persistent kernel (one workgroup per CU
+ *       walks over its tiles; what the library itself uses for that tile).
  * All pointers are device pointers; unused ones may be NULL.  Returns an il_status.
  */
 int il_test_gemm(int32_t dtype, const void *A, const void *B, int32_t M, int32_t N, int32_t K, int32_t lda,

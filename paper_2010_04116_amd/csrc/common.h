@@ -99,7 +99,7 @@ struct GemmArgs {
   uint32_t a_bytes, b_bytes;  // operand extents in bytes (filled by the bf16 front end)
   int k_begin, k_end; // reduction range [k_begin, k_end); both 0 = all of K (used by split-K)
   int tile;           // bf16: 0 = choose by shape, 1 = 256x256, 2 / 3 = 128x128 with 2 / 4 stages, 4 / 5 = 64x64 with 2 / 4,
-                      // 6 = 256x128, 7 = 128x256 (three stages)
+                      // 6 = 256x128, 7 = 128x256 (three stages), 8 = 256x256 persistent
   int beta;           // EPI_WGRAD: accumulate into C
 };
 
