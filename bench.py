@@ -5,10 +5,11 @@ A step is the whole hot path: K x (il_stage_forward + il_head_xent) and the n-wi
 truncated backward il_stage_backward_nwise for k = K..1, all parameter gradients final,
 on seeded synthetic tokens already resident in HBM.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps 20] [--warmup 5] [--workload small] [--n N] [--also medium]
+    python bench.py [--gpus 1] [--steps 20] [--warmup 5] [--workload large] [--n N] [--also medium,many_head,small]
 
-`value` is the workload named by --workload (default: the Small configuration); the workloads
-named by --also are measured the same way and reported under "other_workloads".
+`value` is the workload named by --workload (default: Large, n = 2 - the largest single-GPU
+configuration, the one the MFMA-utilisation target is about); the workloads named by --also are
+measured the same way and reported under "other_workloads".
 """
 import argparse
 import json
@@ -25,14 +26,19 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_F32_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
 
-# HBM-side bytes per GEMM kernel launch (average over the launches of one step), from two
+# HBM-side bytes per GEMM kernel launch (average over the GEMM launches of one step), from two
 # rocprofv3 --pmc runs of this script (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same
-# counter reads for a 256 MiB device-to-device copy (--calibration-copy-mib 256): see
-# profiles/traffic_small_bf16_n2.md.  bench.py cannot run the profiler on itself, so the
-# figure is carried here for the workload it was measured on and is null for any other.
+# counter reads for the library's streaming copy of known size (--calibration-copy-mib 256): see
+# profiles/traffic_<workload>.md.  bench.py cannot run the profiler on itself, so the figures are
+# carried here for the workloads they were measured on and are null for any other.
 MEASURED_TRAFFIC = {
     "small_bf16_n2": 41.88e6,   # 32.18 MB read + 9.70 MB written per launch, 768 launches
 }
+
+# which roofline bounds a kernel class, and the peak its fraction is taken against
+CLASS_BOUND = {"gemm_fwd": "mfma", "gemm_dgrad": "mfma", "gemm_wgrad": "mfma", "gemm_head": "mfma",
+               "attn_fwd": "mfma", "attn_bwd": "mfma", "ln_fwd": "hbm", "ln_bwd": "hbm", "colsum": "hbm",
+               "xent": "hbm", "misc": "hbm"}
 
 
 def minimal_flops(w):
@@ -73,10 +79,12 @@ def time_steps(st, steps, warmup):
     return e0.elapsed_time(e1) / steps, wall / steps
 
 
-def kernel_table(w, flat, steps):
-    """Per-kernel-class HIP-event times from the library's own profiling hooks."""
+def class_table(w, dev_params, steps, mode):
+    """Per-kernel-class figures from the library's own timers.  mode 1: everything in line on one
+    stream, HIP events around each launch group and attached to each GEMM dispatch.  mode 2: the step
+    as it is timed (two streams), timers attached to the GEMM dispatches only."""
     from paper_2010_04116_amd import binding
-    st = binding.Step(w, flat, profile=True)
+    st = binding.Step(w, dev_params, profile=mode)
     st.set_inputs(*INPUTS)
     st.run()
     binding.il_profile_read(st.ctx)             # discard warm-up
@@ -85,89 +93,146 @@ def kernel_table(w, flat, steps):
     prof = binding.il_profile_read(st.ctx)
     st.close()
     for v in prof.values():
-        v["steps"] = steps
-        v["ms_per_step"] = v["ms"] / steps
-        v["flops_per_step"] = v["flops"] / steps
-        v["bytes_per_step"] = v["bytes"] / steps
-        v["launches_per_step"] = v["launches"] / steps
+        for key in ("ms", "flops", "bytes", "launches", "kernel_ms"):
+            v[key + "_per_step"] = v[key] / steps
     return prof
 
 
 def cpu_baseline(w, params, x0, tgt):
-    """The float64 oracle, as it stands, on the host cores, on a bounded sample: the
-    first `b` sequences of the batch through the whole model (every per-token cost is
-    the same as in the full batch, so tokens/s is directly comparable)."""
+    """The float64 oracle, as it stands, on the host cores, on a bounded sample of the workload
+    (about 10-30 s of CPU work at the ~0.1 TFLOP/s the numpy oracle reaches).  Small workloads: the
+    first b sequences of the batch through the whole model (every per-token cost is the same as in the
+    full batch, so tokens/s is directly comparable).  Workloads whose single sequence costs more than
+    that budget: sequence 0 through component 1 and head 1 alone (forward, loss, local backward), scaled
+    to the whole step by the ratio of algorithmic flops - the sample line says so."""
     from oracle import interlock as O
-    # aim at ~10-30 s: assume ~100 GFLOP/s float64 on the host
-    full = minimal_flops(w)
-    b = int(max(1, min(w.B, np.floor(w.B * 2.0e12 / full))))
-    ws = w.with_(B=b)
-    xs = x0[: b * w.T]
-    ts = tgt[:b]
+    per_seq = minimal_flops(w.with_(B=1))
+    cores = len(os.sched_getaffinity(0))
+    if per_seq <= 3.0e12:
+        b = int(max(1, min(w.B, np.floor(2.0e12 / per_seq))))
+        ws = w.with_(B=b)
+        t0 = time.perf_counter()
+        O.nwise_streams(params, x0[: b * w.T], tgt[:b], ws.B, ws.T, ws.H, ws.n)
+        dt = time.perf_counter() - t0
+        return {"value": b * w.T / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle", "seconds": dt,
+                "extrapolated": False,
+                "sample": f"first {b} of {w.B} sequences ({b * w.T} tokens), all {w.K} components and heads, "
+                          f"n={w.n}, float64 numpy stream path, one run"}
+    ws = w.with_(B=1, K=1, n=1)
+    sub = {"components": params["components"][:1], "heads": params["heads"][:1],
+           "head_blocks": params["head_blocks"][:1]}
     t0 = time.perf_counter()
-    O.nwise_streams(params, xs, ts, ws.B, ws.T, ws.H, ws.n)
+    O.nwise_streams(sub, x0[: w.T], tgt[:1], 1, w.T, w.H, 1)
     dt = time.perf_counter() - t0
-    return {"value": b * w.T / dt, "unit": "tokens/s", "cores": len(os.sched_getaffinity(0)),
-            "kind": "oracle", "seconds": dt,
-            "sample": f"first {b} of {w.B} sequences ({b * w.T} tokens), all {w.K} components and heads, "
-                      f"n={w.n}, float64 numpy stream path, one run"}
+    ratio = per_seq / minimal_flops(ws)
+    return {"value": w.T / (dt * ratio), "unit": "tokens/s", "cores": cores, "kind": "oracle", "seconds": dt,
+            "extrapolated": True, "flop_ratio_step_over_sample": ratio,
+            "sample": f"sequence 0 ({w.T} tokens) through component 1 ({w.L} blocks) and head 1 only, n=1 "
+                      f"(forward, loss, local backward), float64 numpy stream path, one run of {dt:.1f} s; scaled to "
+                      f"the whole step (all {w.K} components and heads, n={w.n}) by the ratio of algorithmic "
+                      f"flops, {ratio:.2f}"}
 
 
 INPUTS = None
 
 
-def measure(w, steps, warmup):
-    """Time `steps` whole steps of workload w, then the per-class table in a profiling context."""
+def measure(w, steps, warmup, peaks):
+    """Time `steps` whole steps of workload w, then the GEMM kernels inside the same two-stream step,
+    then the per-class table in a single-stream profiling context."""
     global INPUTS
+    import torch
     from paper_2010_04116_amd import binding, synth
     params = synth.make_params(w)                      # N(0,0.02) weights, biases 0, LN 1/0
     inp, tgt = synth.make_tokens(w)
     x0 = synth.make_x0(w, inp)
-    flat = binding.pack_params(w, params)
+    flat = torch.from_numpy(binding.pack_params(w, params))
+    dev_params = (flat.to(torch.bfloat16) if w.dtype == "bf16" else flat).to("cuda:0").contiguous()
+    del flat
     INPUTS = (x0, tgt)
 
-    st = binding.Step(w, flat)
+    st = binding.Step(w, dev_params)
     st.set_inputs(x0, tgt)
     ms, wall_ms = time_steps(st, steps, warmup)
     losses = st.results()["losses"]
     st.close()
+    del st
     # uniform random tokens: every loss sits at ln V plus half the logit variance, which grows with depth
     assert np.all(np.isfinite(losses)) and np.all(losses > np.log(w.V) - 0.5) and np.all(losses < 4 * np.log(w.V)), losses
 
-    prof = kernel_table(w, flat, max(2, min(steps, 5)))
+    psteps = max(2, min(steps, 5))
     flops = minimal_flops(w)
+    bf = w.dtype == "bf16"
+    prof = class_table(w, dev_params, psteps, 1)
     gemm = [k for k in prof if k.startswith("gemm")]
     g_fl = sum(prof[k]["flops_per_step"] for k in gemm)
     g_by = sum(prof[k]["bytes_per_step"] for k in gemm)
     g_n = sum(prof[k]["launches_per_step"] for k in gemm)
-    if w.dtype == "bf16":
+    peak = PEAK_BF16_TFLOPS if bf else PEAK_F32_TFLOPS
+    if bf:
         # events attached to each MFMA GEMM dispatch: the kernel's own execution time
-        g_ms = sum(prof[k]["kernel_ms"] for k in gemm) / prof[gemm[0]]["steps"]
-        peak, how = PEAK_BF16_TFLOPS, "HIP events attached to each GEMM kernel dispatch"
+        iso_ms = sum(prof[k]["kernel_ms_per_step"] for k in gemm)
+        instep = class_table(w, dev_params, psteps, 2)
+        g_ms = sum(instep[k]["kernel_ms_per_step"] for k in gemm)
+        how = ("HIP events attached to each GEMM kernel dispatch (hipExtLaunchKernelGGL) inside the two-stream step "
+               "as it is timed for `value`: other kernels run beside the GEMMs; `isolated` is the same launches "
+               "with the whole step in line on one stream")
     else:
-        g_ms = sum(prof[k]["ms_per_step"] for k in gemm)
-        peak, how = PEAK_F32_TFLOPS, "HIP events recorded around each GEMM launch"
+        iso_ms = g_ms = sum(prof[k]["ms_per_step"] for k in gemm)
+        instep = None
+        how = "HIP events recorded around each GEMM launch, single stream"
     achieved = g_fl / (g_ms * 1e-3) / 1e12 if g_ms > 0 else 0.0
+    iso = g_fl / (iso_ms * 1e-3) / 1e12 if iso_ms > 0 else 0.0
+    traffic = MEASURED_TRAFFIC.get(f"{w.name}_{w.dtype}_n{w.n}")
+    roof = {"bound": "mfma" if bf else "alu",
+            "kernel": "gemm_dma_kernel / gemm_persist_kernel: every GEMM launch of one step (forward, dgrad, wgrad, head)"
+            if bf else "gemm_simt_kernel: every GEMM launch of one step",
+            "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+            "traffic": traffic, "launches_per_step": g_n, "avg_launch_ms": g_ms / max(g_n, 1),
+            "algorithmic_gflop_per_launch": g_fl / max(g_n, 1) / 1e9,
+            "algorithmic_bytes_per_launch": g_by / max(g_n, 1),
+            "traffic_over_algorithmic_bytes": (traffic / (g_by / max(g_n, 1))) if traffic else None,
+            "hbm_gbs_from_traffic": (traffic / (g_ms / max(g_n, 1) * 1e-3) / 1e9) if traffic and g_ms > 0 else None,
+            "frac_is": "in-step" if bf else "single stream",
+            "isolated": {"achieved": iso, "frac": iso / peak, "avg_launch_ms": iso_ms / max(g_n, 1)},
+            "timing": how}
+    if bf and peaks:
+        roof["measured_peak"] = peaks["mfma_only_tflops"]
+        roof["frac_of_measured_peak"] = achieved / peaks["mfma_only_tflops"]
+
+    kernels = {}
+    for k, v in prof.items():
+        bound = CLASS_BOUND.get(k, "hbm")
+        if not bf and bound == "mfma":
+            bound = "alu"
+        t = v["ms_per_step"] * 1e-3
+        e = {"ms_per_step": round(v["ms_per_step"], 4), "launches": v["launches_per_step"], "bound": bound}
+        if bound in ("mfma", "alu"):
+            e["tflops"] = v["flops_per_step"] / t / 1e12 if t > 0 and v["flops_per_step"] else None
+            e["frac"] = e["tflops"] / peak if e["tflops"] else None
+            if bf and k in gemm:                       # the kernel alone, and inside the two-stream step
+                tk, ti = v["kernel_ms_per_step"] * 1e-3, instep[k]["kernel_ms_per_step"] * 1e-3
+                e["kernel_tflops"] = v["flops_per_step"] / tk / 1e12 if tk > 0 else None
+                e["kernel_frac"] = e["kernel_tflops"] / peak if e["kernel_tflops"] else None
+                e["in_step_kernel_tflops"] = v["flops_per_step"] / ti / 1e12 if ti > 0 else None
+                e["in_step_kernel_frac"] = e["in_step_kernel_tflops"] / peak if e["in_step_kernel_tflops"] else None
+        else:
+            e["gbs"] = v["bytes_per_step"] / t / 1e9 if t > 0 and v["bytes_per_step"] else None
+            e["frac"] = e["gbs"] / PEAK_HBM_GBS if e["gbs"] else None
+            if e["gbs"] and peaks:
+                e["frac_of_measured_copy"] = e["gbs"] / peaks["stream_copy_gbs"]
+        kernels[k] = e
     res = {
         "ms_per_step": ms, "wall_ms_per_step": wall_ms, "tokens_per_s": w.N / (ms * 1e-3),
         "mfma_utilisation_pct_of_bf16_peak": 100.0 * flops / (ms * 1e-3) / (PEAK_BF16_TFLOPS * 1e12),
         "algorithmic_tflop_per_step": flops / 1e12,
-        "roofline": {"bound": "mfma" if w.dtype == "bf16" else "alu",
-                     "kernel": "gemm_dma_kernel / gemm_persist_kernel: every GEMM launch of one step (forward, dgrad, wgrad, head)"
-                     if w.dtype == "bf16" else "gemm_simt_kernel: every GEMM launch of one step",
-                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
-                     "traffic": MEASURED_TRAFFIC.get(f"{w.name}_{w.dtype}_n{w.n}"),
-                     "launches_per_step": g_n, "avg_launch_ms": g_ms / max(g_n, 1),
-                     "algorithmic_gflop_per_launch": g_fl / max(g_n, 1) / 1e9,
-                     "algorithmic_bytes_per_launch": g_by / max(g_n, 1), "timing": how},
-        "kernels": {k: {"ms_per_step": round(v["ms_per_step"], 4), "launches": v["launches_per_step"],
-                        "tflops": (v["flops_per_step"] / (v["ms_per_step"] * 1e-3) / 1e12)
-                        if v["ms_per_step"] > 0 and v["flops_per_step"] else None,
-                        "gbs": (v["bytes_per_step"] / (v["ms_per_step"] * 1e-3) / 1e9)
-                        if v["ms_per_step"] > 0 and v["bytes_per_step"] else None}
-                    for k, v in prof.items()},
+        "algorithmic_hbm_gbs": (sum(v["bytes_per_step"] for v in prof.values()) / (ms * 1e-3) / 1e9),
+        "roofline": roof,
+        "kernels": kernels,
+        "kernels_note": "single-stream profiling context; ms_per_step brackets each launch group with HIP events "
+                        "(upper bounds: an event costs a few microseconds between launches)",
         "losses": [float(x) for x in losses],
     }
+    del dev_params
     res["optimizer"] = optimizer_line(w)
     res["embedding"] = embedding_line(w)
     return res, params, x0, tgt
@@ -242,6 +307,24 @@ def embedding_line(w, reps=10):
             "peak": PEAK_HBM_GBS, "unit": "GB/s"}
 
 
+def measured_peaks(copy_mib=1024):
+    """What the board itself reaches: a matrix-unit-only loop and a streaming copy (the library's
+    micro-benchmarks), reported beside the nominal peaks the roofline fractions use."""
+    import torch
+    from paper_2010_04116_amd import binding
+    n = copy_mib << 20
+    src = torch.ones(n, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty_like(src)
+    st = torch.cuda.current_stream().cuda_stream
+    mf = max(binding.il_measure_mfma_peak(dst, 20000, stream=st) for _ in range(2))
+    cp = max(binding.il_measure_copy_peak(dst, src, n, 10, stream=st) for _ in range(2))
+    del src, dst
+    return {"mfma_only_tflops": mf, "mfma_only_frac_of_nominal": mf / PEAK_BF16_TFLOPS,
+            "stream_copy_gbs": cp, "stream_copy_frac_of_nominal": cp / PEAK_HBM_GBS,
+            "how": f"il_measure_mfma_peak (512 workgroups x 4 wavefronts x 80000 MFMAs 32x32x16 bf16, registers only); "
+                   f"il_measure_copy_peak ({copy_mib} MiB device-to-device, read + written bytes, best of 2 x 10 launches)"}
+
+
 def config_of(w):
     from paper_2010_04116_amd import synth
     return {"workload": f"{w.name}_{w.dtype}_n{w.n}", "K": w.K, "blocks_per_component": w.L,
@@ -255,14 +338,17 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="small")
+    ap.add_argument("--workload", default="large")
     ap.add_argument("--n", type=int, default=0, help="override the workload's window")
-    ap.add_argument("--also", default="medium",
-                    help="comma-separated further workloads reported under other_workloads ('' = none)")
+    ap.add_argument("--also", default="medium,many_head,small",
+                    help="comma-separated further workloads reported under other_workloads ('none' = none); "
+                         "name:n overrides the window, e.g. large:6")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-peaks", action="store_true", help="skip the MFMA-only / streaming-copy micro-benchmarks")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
-                    help="first run one device-to-device copy of this many MiB (a kernel of known HBM "
-                         "traffic, against which rocprofv3's FETCH_SIZE / WRITE_SIZE counters are scaled)")
+                    help="first run two launches of the library's streaming copy kernel over this many MiB "
+                         "(a kernel of known HBM traffic, against which rocprofv3's FETCH_SIZE / WRITE_SIZE "
+                         "counters are scaled)")
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (--gpus 1); depthwise sharding "
@@ -270,18 +356,19 @@ def main():
     if int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: launched with WORLD_SIZE > 1; this build runs on exactly one GPU")
 
-    from paper_2010_04116_amd import synth
+    from paper_2010_04116_amd import binding, synth
     if a.calibration_copy_mib > 0:
         import torch
         src = torch.ones(a.calibration_copy_mib << 20, dtype=torch.uint8, device="cuda:0")
         dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
+        binding.il_measure_copy_peak(dst, src, a.calibration_copy_mib << 20, 1,
+                                     stream=torch.cuda.current_stream().cuda_stream)
         del src, dst
+    peaks = None if a.no_peaks else measured_peaks()
     w = synth.WORKLOADS[a.workload]
     if a.n:
         w = w.with_(n=a.n)
-    res, params, x0, tgt = measure(w, a.steps, a.warmup)
+    res, params, x0, tgt = measure(w, a.steps, a.warmup, peaks)
     out = {
         "metric": "tokens/sec per n-wise train step at 1 GPU",
         "value": res.pop("tokens_per_s"), "unit": "tokens/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
@@ -289,16 +376,25 @@ def main():
         "dtype": w.dtype, "data": "synthetic", "config": config_of(w),
     }
     out.update(res)
+    if peaks:
+        out["measured_peaks"] = peaks
+    out["target"] = {"mfma_utilisation_pct": 50.0, "met": out["mfma_utilisation_pct_of_bf16_peak"] >= 50.0,
+                     "note": "north star: >= 50 % of bf16 MFMA peak on the GEMM-dominated configurations"}
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, params, x0.astype(np.float64), tgt)
     del params, x0, tgt
     others = {}
-    for name in [x for x in a.also.split(",") if x and x != "none" and x != a.workload]:
+    for spec in [x for x in a.also.split(",") if x and x != "none"]:
+        name, _, nn = spec.partition(":")
         wo = synth.WORKLOADS[name]
-        ro = measure(wo, min(a.steps, 10), min(a.warmup, 3))[0]
-        ro.pop("kernels"); ro.pop("losses")
+        if nn:
+            wo = wo.with_(n=int(nn))
+        if (wo.name, wo.n) == (w.name, w.n):
+            continue
+        ro = measure(wo, min(a.steps, 10), min(a.warmup, 3), peaks)[0]
+        ro.pop("losses")
         ro["config"] = config_of(wo)
-        others[wo.name] = ro
+        others[f"{wo.name}_{wo.dtype}_n{wo.n}"] = ro
     if others:
         out["other_workloads"] = others
     print(json.dumps(out))

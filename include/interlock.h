@@ -95,7 +95,10 @@ typedef struct il_config {
   float ln_eps;                 /* e.g. 1e-5                                         */
   int32_t head_chunk;           /* token rows per head chunk (0 = library default);
                                    only a [head_chunk, vocab] logits tile ever exists */
-  int32_t profile;              /* nonzero: record per-kernel-class HIP event times   */
+  int32_t profile;              /* 0: off.  1: HIP event times per kernel class (read with
+                                   il_profile_read, interlock_test.h); everything then runs on
+                                   il_config.stream alone.  2: the step runs exactly as with 0
+                                   (both streams); only the bf16 GEMM dispatches carry timers */
   int32_t head_blocks;          /* Transformer blocks inside every auxiliary head, in front
                                    of its d_model -> vocab map (0 = the bare linear head;
                                    the paper's Transformer runs use 2, App. B)          */
@@ -116,7 +119,9 @@ typedef struct il_config {
  * Limits (IL_E_SHAPE otherwise): d_model a multiple of n_heads with head width
  * d_model / n_heads in {16, 32, 64, 128}, or 256 in bf16 mode; d_model <= 2048; batch*seq <= 2^24; vocab <= 2^24;
  * in bf16 mode d_model, d_mlp and vocab multiples of 8, batch*seq and head_chunk multiples of
- * 64.  At most 16 merged gradient streams may be live at one component.
+ * 64.  At most 16 merged gradient streams may be live at one component.  Every GEMM operand stays
+ * below 2 GiB: streams * batch*seq * max(3 d_model, d_mlp), d_model * vocab, head_chunk * vocab
+ * elements of `dtype`.
  * The workspace must be 256-byte aligned.
  */
 int il_init(il_config *cfg, il_ctx **out);
@@ -133,12 +138,16 @@ int il_stage_forward(il_ctx *ctx, int32_t k, const float *x_in, float *x_out);
 /*
  * Auxiliary head k and its local loss L_k = xent(h_k(x_k), y) (Sec. 3, the equation
  * defining the local loss).  x_k: device fp32 [N, d_model]; targets: device int32 [N],
- * each in [0, vocab); loss_out: device fp32 scalar (mean over N, natural log).
+ * each in [0, vocab) - a target outside that range marks an ignored position: it adds nothing to the
+ * loss or to any gradient, and the mean still divides by N; loss_out: device fp32 scalar (mean over N,
+ * natural log).
  * Writes dL_k/dW_head,k (and the gradients of the head's own blocks) into grads and keeps
  * dL_k/dx_k - propagated back through those blocks - in the workspace as the
  * gradient stream of head k (age 0) for il_stage_backward_nwise.  Logits and
  * probabilities exist only one [head_chunk, vocab] tile at a time.
- * Order: after il_stage_forward(k) of the same step.
+ * Order: after il_stage_forward(k) of the same step, in any order among the heads; with
+ * head_blocks > 0 also before the step's first il_stage_backward_nwise (IL_E_STATE otherwise: the
+ * head's own blocks are differentiated in the scratch the backward uses).
  */
 int il_head_xent(il_ctx *ctx, int32_t k, const float *x_k, const int32_t *targets, float *loss_out);
 
@@ -180,41 +189,6 @@ int il_free(il_ctx *ctx);
  * Either array may be NULL.  Returns IL_E_ARG for n outside [1,K] or unknown route.
  */
 int il_routing_plan(int32_t K, int32_t n, int32_t route, int32_t *live, int32_t *passes);
-
-/*
- * Profiling (cfg.profile != 0): synchronises the stream and returns, per kernel class,
- * launches and total milliseconds since the last call, measured with HIP events recorded
- * on the library's stream before and after each launch group (`ms`; this includes the few
- * microseconds an event costs between launches), the algorithmic flops and bytes of those
- * launches, and for the bf16 GEMM classes `kernel_ms`: the execution time of the MFMA GEMM
- * kernels alone, from events attached to each dispatch (0 for the other classes).  In
- * profiling mode the heads run on the caller's stream instead of the internal side stream.
- * `names` receives pointers to static strings; any output array may be NULL.  Returns the
- * number of classes written (<= cap), or a negative il_status.
- */
-int il_profile_read(il_ctx *ctx, int32_t cap, const char **names, int64_t *launches, double *ms,
-                    double *flops, double *bytes, double *kernel_ms);
-
-/*
- * Kernel-level test hook: one GEMM launch of the library's own kernels, outside any step, so
- * that tests and micro-benchmarks can reach each tile configuration and epilogue directly.
- *   C[M,N] = epilogue( sum_k A(m,k) B(k,n) )
- * dtype: il_dtype of A, B (and of C for the bf16/fp32-typed epilogues, see `epi`);
- * a_kmajor / b_kmajor: 0 = operand stored [rows, K] row-major, 1 = stored [K, rows] row-major;
- * epi: 0 store (T) | 1 +bias (T) | 2 +bias, C = pre-activation, C2 = GELU (T, T) |
- *      3 +bias +res (fp32 out) | 4 * GELU'(aux[row % aux_wrap]) (T) | 5 store fp32 |
- *      6 C = scale*acc (+ C if beta) (fp32);
- * tile: 0 = library's choice, else (bf16 only; "+4" = four wavefronts that only load)
- *       1 = 256x256 / 8+4 wavefronts, 2 = 128x128 / 4+4, two K steps staged, 3 = 128x128 / 4+4, four staged,
- *       4 = 64x64 / 4 wavefronts, 5 = 64x64 / 4+4, four staged, 6 = 256x128 / 8+4, three staged,
- *       7 = 128x256 / 8+4, three staged, 8 = 256x256 / 8+4 as a persistent kernel (one workgroup per CU
- *       walks over its tiles; what the library itself uses for that tile).
- * All pointers are device pointers; unused ones may be NULL.  Returns an il_status.
- */
-int il_test_gemm(int32_t dtype, const void *A, const void *B, int32_t M, int32_t N, int32_t K, int32_t lda,
-                 int32_t ldb, int32_t a_kmajor, int32_t b_kmajor, int32_t epi, void *C, void *C2, int32_t ldc,
-                 const void *bias, const float *res, const void *aux, int32_t aux_wrap, float scale,
-                 int32_t beta, int32_t tile, void *stream);
 
 /* ---- input embedding of the first module (App. B: the embedding matrix in front of the blocks) ---- */
 

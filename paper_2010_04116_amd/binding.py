@@ -24,7 +24,7 @@ ROUTES = {"window_sum": 0, "far_head": 1, "mean_local_far": 2}
 SYMBOLS = ("il_init", "il_stage_forward", "il_head_xent", "il_stage_backward_nwise", "il_free",
            "il_routing_plan", "il_profile_read", "il_status_string", "il_test_gemm", "il_lr_schedule",
            "il_adam_step", "il_embed_forward", "il_embed_backward", "il_set_accumulation",
-           "il_time_per_batch", "il_optimal_microbatches")
+           "il_time_per_batch", "il_optimal_microbatches", "il_measure_mfma_peak", "il_measure_copy_peak")
 
 
 class il_config(C.Structure):
@@ -75,6 +75,8 @@ def load():
     lib.il_time_per_batch.argtypes = [i32, i32, i32, C.c_double, C.c_double]
     lib.il_time_per_batch.restype = C.c_double
     lib.il_optimal_microbatches.argtypes = [i32, i32, C.c_double, C.c_double, i32]
+    lib.il_measure_mfma_peak.argtypes = [vp, i32, vp, C.POINTER(C.c_double)]
+    lib.il_measure_copy_peak.argtypes = [vp, vp, C.c_size_t, i32, vp, C.POINTER(C.c_double)]
     lib.il_status_string.argtypes = [C.c_int]
     lib.il_status_string.restype = C.c_char_p
     for name in SYMBOLS:
@@ -99,7 +101,7 @@ def il_routing_plan(K: int, n: int, route: str = "window_sum"):
 
 
 def make_config(w: synth.Workload, route: str = "window_sum", head_chunk: int = 0,
-                profile: bool = False, ln_eps: float = 1e-5) -> il_config:
+                profile: int = 0, ln_eps: float = 1e-5) -> il_config:
     cfg = il_config()
     cfg.K, cfg.blocks_per_component, cfg.d_model, cfg.n_heads = w.K, w.L, w.d, w.H
     cfg.d_mlp, cfg.vocab, cfg.batch, cfg.seq, cfg.n = w.m, w.V, w.B, w.T, w.n
@@ -212,6 +214,21 @@ def il_optimal_microbatches(A: int, N: int, c0: float = 0.025, c1: float = 1.279
     return rc
 
 
+def il_measure_mfma_peak(scratch, iters: int = 20000, stream=None) -> float:
+    """Achieved TFLOP/s of the matrix-unit-only loop (synchronises)."""
+    out = C.c_double()
+    _check(load().il_measure_mfma_peak(_ptr(scratch), iters, stream, C.byref(out)), "il_measure_mfma_peak")
+    return out.value
+
+
+def il_measure_copy_peak(dst, src, nbytes: int, reps: int = 10, stream=None) -> float:
+    """Achieved GB/s (read + written) of the streaming copy kernel (synchronises)."""
+    out = C.c_double()
+    _check(load().il_measure_copy_peak(_ptr(dst), _ptr(src), nbytes, reps, stream, C.byref(out)),
+           "il_measure_copy_peak")
+    return out.value
+
+
 def il_lr_schedule(step: int, d_model: int, warmup_steps: int = 4000) -> float:
     return float(load().il_lr_schedule(step, d_model, warmup_steps))
 
@@ -293,17 +310,22 @@ class Step:
     """Device buffers + context for one workload; `run()` performs one whole n-wise step
     through the five library calls."""
 
-    def __init__(self, w: synth.Workload, flat_params: np.ndarray, route: str = "window_sum",
-                 head_chunk: int = 0, profile: bool = False, device: str = "cuda:0", stream=None):
+    def __init__(self, w: synth.Workload, flat_params, route: str = "window_sum",
+                 head_chunk: int = 0, profile: int = 0, device: str = "cuda:0", stream=None):
         import torch
         self.torch = torch
         self.w = w
-        self.dev = torch.device(device)
+        self.dev = torch.device(device if ":" in device else device + ":0")
         load()
         cfg = make_config(w, route, head_chunk, profile)
         pb, gb, wb = query_sizes(cfg)
-        p = torch.from_numpy(flat_params)
-        self.params = (p.to(torch.bfloat16) if w.dtype == "bf16" else p).to(self.dev).contiguous()
+        tt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+        if isinstance(flat_params, torch.Tensor):      # already on the device in the run's element type: shared
+            if flat_params.device != self.dev or flat_params.dtype != tt or not flat_params.is_contiguous():
+                raise ValueError("device parameters must be a contiguous tensor of the workload's dtype on " + device)
+            self.params = flat_params
+        else:
+            self.params = torch.from_numpy(flat_params).to(tt).to(self.dev).contiguous()
         assert self.params.numel() * self.params.element_size() == pb
         self.grads = torch.empty(gb // 4, dtype=torch.float32, device=self.dev)
         self.workspace = torch.empty(wb, dtype=torch.uint8, device=self.dev)

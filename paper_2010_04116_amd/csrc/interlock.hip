@@ -7,6 +7,7 @@
 // them in a single launch; where the live slots are not adjacent the component's backward
 // runs once per contiguous range and the later ranges accumulate.
 #include "../../include/interlock.h"
+#include "../../include/interlock_test.h"
 
 #include <cmath>
 #include <cstdlib>
@@ -161,7 +162,7 @@ struct BlockSave {  // workspace pointers of one block's saved activations
   float *xs, *st1, *lse, *a, *st2;
   char *h1, *qkv, *o, *h2, *u, *gl;
 };
-struct ProfRec { int cls; bool kernel; hipEvent_t e0, e1; KernelTimer kt; };
+struct ProfRec { int cls; bool kernel, bracket; hipEvent_t e0, e1; KernelTimer kt; };
 
 }  // namespace
 
@@ -301,6 +302,9 @@ struct Scope {  // brackets a group of launches with events when profiling is on
   Scope(il_ctx *ctx, int cls_, double flops, double bytes) : c(ctx), cls(cls_) {
     if (!c->cfg.profile) return;
     c->flops[cls] += flops; c->bytes[cls] += bytes;
+    // mode 2: the step runs as it does unprofiled (two streams); only the bf16 GEMM dispatches carry timers
+    const bool in_step = c->cfg.profile == 2;
+    if (in_step && !(c->cfg.dtype == IL_BF16 && cls <= KC_GEMM_HEAD)) return;
     if (c->nrec == c->recs.size()) {
       ProfRec n{};
       if (hipEventCreate(&n.e0) != hipSuccess || hipEventCreate(&n.e1) != hipSuccess ||
@@ -312,13 +316,14 @@ struct Scope {  // brackets a group of launches with events when profiling is on
     r->cls = cls;
     // bf16 GEMM scopes also time their MFMA kernel launch by itself (events on the dispatch)
     r->kernel = c->cfg.dtype == IL_BF16 && cls <= KC_GEMM_HEAD;
+    r->bracket = !in_step;
     if (r->kernel) gemm_time_next(&r->kt);
-    hipEventRecord(r->e0, c->stream);
+    if (r->bracket) hipEventRecord(r->e0, c->stream);
   }
   ~Scope() {
     if (!r) return;
     if (gemm_time_next(nullptr)) r->kernel = false;  // no MFMA GEMM was launched in this scope
-    hipEventRecord(r->e1, c->stream);
+    if (r->bracket) hipEventRecord(r->e1, c->stream);
   }
 };
 
@@ -445,7 +450,7 @@ int linear_wgrad(il_ctx *c, const Run &cp, const void *x, const void *dy, int Ki
   if (cp.nweighted == 0) return IL_OK;  // pass-through streams only: nothing is credited
   // (with the block tail on the side stream every operand is materialised: the scratch it would
   // be read from is rewritten by the next block meanwhile)
-  const bool in_place = cp.nweighted == 1 && cp.wscale == 1.f && !keep && (c->cfg.profile || c->tail_inline);
+  const bool in_place = cp.nweighted == 1 && cp.wscale == 1.f && !keep && (c->cfg.profile == 1 || c->tail_inline);
   const char *dys = in_place ? (const char *)dy + (size_t)cp.first_weighted * c->N * Nout * c->eb : c->YS[slot];
   {
     // queued: two of a block's four reductions are ready at the same point of the backward and
@@ -498,11 +503,11 @@ int launch_wgrads(il_ctx *c, const GemmArgs *list, int n) {
 // 128x128 tiles, two workgroups per CU (0.96 us per 64-deep step), split until about 512 tiles;
 // or 256x256 tiles, one per CU (1.6 us per step, 2.6x the flops), split until about 256 tiles.
 // gemm_bf16_batch then picks the matching tile from the tile counts of the split problem.
-int choose_splits(il_ctx *c, int M, int N, int K) {
+int choose_splits(il_ctx *c, size_t skws_floats, int M, int N, int K) {
   if (c->cfg.dtype != IL_BF16) return 1;
   const long t128 = (long)((M + 127) / 128) * ((N + 127) / 128);
   const long t256 = (long)((M + 255) / 256) * ((N + 255) / 256);
-  const long cap = std::min<long>(kMaxBatch, (long)(c->skws_floats / ((size_t)M * N)));
+  const long cap = std::min<long>(kMaxBatch, (long)(skws_floats / ((size_t)M * N)));
   auto reduce_us = [&](long sp) { return sp < 2 ? 0.0 : 6.0 + (double)(sp + 1) * M * N * 4.0 / 3.0e6; };
   const double steps = K / 64.0;
   long sp128 = 1;
@@ -572,7 +577,7 @@ int block_backward(il_ctx *c, const Run &cp, const BlockOff &b, const BlockSave 
   c->jobs.count = 0;
   c->pending.count = 0;
   c->pending_bytes = 0;
-  const bool async_tail = !c->cfg.profile && !c->tail_inline;
+  const bool async_tail = c->cfg.profile != 1 && !c->tail_inline;
   const int par = c->bparity;
   if (async_tail) {
     if ((rc = ensure_side(c))) return rc;
@@ -650,6 +655,7 @@ int validate(const il_config *cfg) {
   if (cfg->dtype != IL_F32 && cfg->dtype != IL_BF16) return IL_E_ARG;
   if (cfg->route < 0 || cfg->route > IL_ROUTE_MEAN_LOCAL_FAR) return IL_E_ARG;
   if (!(cfg->ln_eps > 0.f)) return IL_E_ARG;
+  if (cfg->profile < 0 || cfg->profile > 2) return IL_E_ARG;
   if (cfg->head_chunk < 0 || cfg->head_blocks < 0 || cfg->head_blocks > 64 || cfg->reserved != 0) return IL_E_ARG;
   if (cfg->d_model % cfg->n_heads) return IL_E_SHAPE;
   const int dh = cfg->d_model / cfg->n_heads;
@@ -707,6 +713,15 @@ int il_init(il_config *cfg, il_ctx **out) {
   c->main_stream = c->stream;
   rc = build_plan(c->K, cfg->n, cfg->route, c->plan);
   if (rc) { delete c; return rc; }
+  {
+    // every GEMM operand is addressed through a 32-bit buffer descriptor: below 2 GiB each
+    const unsigned long long lim = 0x7FFFFFFFull, eb = c->eb, N = c->N, d = c->d, m = c->m, V = c->V;
+    const unsigned long long S = (unsigned long long)std::max(c->plan.maxcnt, 1) * N;
+    if (S * std::max(3 * d, m) * eb >= lim || d * V * eb >= lim || d * m * eb >= lim || 3 * d * d * eb >= lim) {
+      delete c;
+      return IL_E_SHAPE;
+    }
+  }
   int nc = cfg->head_chunk;
   if (nc == 0) {
     nc = std::min(c->N / 2, 2048);
@@ -715,6 +730,10 @@ int il_init(il_config *cfg, il_ctx **out) {
     if (cfg->dtype == IL_BF16 && nc < 64) nc = 64;
   }
   c->Nc = std::min(nc, c->N);
+  if ((unsigned long long)c->Nc * c->V * c->eb >= 0x7FFFFFFFull) {  // the logits tile is a GEMM operand too
+    delete c;
+    return IL_E_SHAPE;
+  }
   const size_t pbytes = layout_params(c) * c->eb;
   const size_t gbytes = pbytes / c->eb * 4;
   const size_t wbytes = layout_workspace(c, cfg->workspace);
@@ -766,10 +785,20 @@ int il_stage_forward(il_ctx *c, int32_t k, const float *x_in, float *x_out) {
   return IL_OK;
 }
 
-int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets, float *loss_out) {
+// The head's scratch: the bf16 / fp32 copy of its input, one logits tile, per-row losses and the
+// split-K partial products of dx.  il_head_xent takes it from the caller's workspace.
+struct HeadScratch {
+  char *xb, *Z; float *rowloss, *skws; size_t skws_floats;
+};
+
+static int head_xent_impl(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets, float *loss_out,
+                          const HeadScratch &hs, bool in_line) {
   if (!c || !x_k || !targets || !loss_out) return IL_E_ARG;
   if (k < 1 || k > c->K) return IL_E_ARG;
   if (!c->fwd_done[k]) return IL_E_STATE;
+  // a head with blocks of its own shares the backward scratch: it may not start once the step's
+  // backward has (the backward could not order itself against it)
+  if (c->Lh > 0 && c->bwd_done[c->K]) return IL_E_STATE;
   const int N = c->N, d = c->d, V = c->V, dt = c->cfg.dtype;
   const size_t eb = c->eb;
   // Head k only needs x_k; it runs on a side stream so that the next component's forward (and,
@@ -778,7 +807,7 @@ int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets,
     il_ctx *c; bool on;
     ~StreamSwap() { if (on) c->stream = c->main_stream; }
   } swap{c, false};
-  if (!c->cfg.profile) {
+  if (c->cfg.profile != 1 && !in_line) {
     { const int rc = ensure_side(c); if (rc) return rc; }
     IL_TRY(hipEventRecord(c->ev_fork, c->main_stream));
     IL_TRY(hipStreamWaitEvent(c->side, c->ev_fork, 0));
@@ -797,37 +826,37 @@ int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets,
   }
   {
     Scope sc(c, KC_MISC, 0, (double)N * d * (4 + eb));
-    IL_TRY(convert_f32(dt, y, c->xb, (size_t)N * d, c->stream));
+    IL_TRY(convert_f32(dt, y, hs.xb, (size_t)N * d, c->stream));
   }
   float *dx = c->dxh + (size_t)(k - 1) * N * d;
   for (int r0 = 0, chunk = 0; r0 < N; r0 += c->Nc, ++chunk) {
     const int rows = std::min(c->Nc, N - r0);
-    const char *xc = c->xb + (size_t)r0 * d * eb;
+    const char *xc = hs.xb + (size_t)r0 * d * eb;
     GemmArgs g = base_args();  // logits tile z = x W_h
     g.A = xc; g.lda = d; g.a_kmajor = 0;
     g.B = P(c, c->hoff[k - 1]); g.ldb = V; g.b_kmajor = 1;
-    g.M = rows; g.N = V; g.K = d; g.epi = EPI_STORE; g.C = c->Z; g.ldc = V;
+    g.M = rows; g.N = V; g.K = d; g.epi = EPI_STORE; g.C = hs.Z; g.ldc = V;
     {
       Scope sc(c, KC_GEMM_HEAD, 2.0 * rows * V * d, gemm_bytes(c, g));
       IL_TRY(gemm(c, g));
     }
     {
       Scope sc(c, KC_XENT, 0, 2.0 * rows * V * eb);
-      IL_TRY(xent_rows(dt, c->Z, targets + r0, rows, V, c->grad_scale / N, c->rowloss + r0, c->stream));
+      IL_TRY(xent_rows(dt, hs.Z, targets + r0, rows, V, c->grad_scale / N, hs.rowloss + r0, c->stream));
     }
     g = base_args();  // dx = dz W_h^T
-    g.A = c->Z; g.lda = V; g.a_kmajor = 0;
+    g.A = hs.Z; g.lda = V; g.a_kmajor = 0;
     g.B = P(c, c->hoff[k - 1]); g.ldb = V; g.b_kmajor = 0;
     g.M = rows; g.N = d; g.K = V; g.epi = EPI_STORE_F32; g.C = dx + (size_t)r0 * d; g.ldc = d;
     {
       Scope sc(c, KC_GEMM_HEAD, 2.0 * rows * V * d, gemm_bytes(c, g));
-      const int sp = choose_splits(c, rows, d, V);
-      if (sp > 1) IL_TRY(gemm_bf16_splitk(g, sp, c->skws, c->stream));
+      const int sp = choose_splits(c, hs.skws_floats, rows, d, V);
+      if (sp > 1) IL_TRY(gemm_bf16_splitk(g, sp, hs.skws, c->stream));
       else IL_TRY(gemm(c, g));
     }
     g = base_args();  // dW_h (+)= x^T dz
     g.A = xc; g.lda = d; g.a_kmajor = 1;
-    g.B = c->Z; g.ldb = V; g.b_kmajor = 1;
+    g.B = hs.Z; g.ldb = V; g.b_kmajor = 1;
     g.M = d; g.N = V; g.K = rows; g.epi = EPI_WGRAD; g.C = Gr(c, c->hoff[k - 1]); g.ldc = V;
     g.beta = chunk > 0 || c->accumulate;
     {
@@ -837,7 +866,7 @@ int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets,
   }
   {
     Scope sc(c, KC_MISC, 0, (double)N * 4);
-    IL_TRY(sum_scalar(c->rowloss, N, 1.f / N, loss_out, c->stream));
+    IL_TRY(sum_scalar(hs.rowloss, N, 1.f / N, loss_out, c->stream));
   }
   if (c->Lh) {
     // dL_k/dy goes back through the head's blocks as a single stream of weight 1 in a slot of its own;
@@ -879,6 +908,12 @@ int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets,
   return IL_OK;
 }
 
+int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets, float *loss_out) {
+  if (!c) return IL_E_ARG;
+  const HeadScratch hs{c->xb, c->Z, c->rowloss, c->skws, c->skws_floats};
+  return head_xent_impl(c, k, x_k, targets, loss_out, hs, false);
+}
+
 int il_stage_backward_nwise(il_ctx *c, int32_t k, float *dx0_out) {
   if (!c) return IL_E_ARG;
   if (k < 1 || k > c->K) return IL_E_ARG;
@@ -887,8 +922,11 @@ int il_stage_backward_nwise(il_ctx *c, int32_t k, float *dx0_out) {
   if (c->bwd_done[k] || (k < c->K && !c->bwd_done[k + 1])) return IL_E_STATE;
   const CompPlan &cp = c->plan.comp[k - 1];
   if (cp.inject_slot >= 0 && !c->head_done[k]) return IL_E_STATE;
-  // join the side stream: head k before its gradient is injected; every head before the step ends
-  for (int j = (k == 1 ? 1 : k); j <= (k == 1 ? c->K : k); ++j)
+  // join the side stream: head k before its gradient is injected; every head before the step ends.
+  // Heads with blocks of their own run a block backward there, over the scratch this call is about to
+  // use: then every head still pending is joined, whatever the order the heads were enqueued in.
+  const bool all_heads = k == 1 || c->Lh > 0;
+  for (int j = (all_heads ? 1 : k); j <= (all_heads ? c->K : k); ++j)
     if (c->head_pending[j]) {
       IL_TRY(hipStreamWaitEvent(c->stream, c->ev_head[j], 0));
       c->head_pending[j] = 0;
@@ -925,12 +963,15 @@ int il_profile_read(il_ctx *c, int32_t cap, const char **names, int64_t *launche
                     double *bytes, double *kernel_ms) {
   if (!c || cap < 0) return IL_E_ARG;
   if (hipStreamSynchronize(c->stream) != hipSuccess) return IL_E_HIP;
+  if (c->side && hipStreamSynchronize(c->side) != hipSuccess) return IL_E_HIP;
   double t[KC_COUNT] = {}, tk[KC_COUNT] = {};
   int64_t n[KC_COUNT] = {};
   for (size_t i = 0; i < c->nrec; ++i) {
     float e = 0.f;
-    if (hipEventElapsedTime(&e, c->recs[i].e0, c->recs[i].e1) != hipSuccess) return IL_E_HIP;
-    t[c->recs[i].cls] += e;
+    if (c->recs[i].bracket) {
+      if (hipEventElapsedTime(&e, c->recs[i].e0, c->recs[i].e1) != hipSuccess) return IL_E_HIP;
+      t[c->recs[i].cls] += e;
+    }
     n[c->recs[i].cls] += 1;
     if (c->recs[i].kernel) {
       if (hipEventElapsedTime(&e, c->recs[i].kt.start, c->recs[i].kt.stop) != hipSuccess) return IL_E_HIP;

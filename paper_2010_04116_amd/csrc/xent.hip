@@ -40,6 +40,11 @@ __global__ __launch_bounds__(256) void xent_rows_kernel(T *z, const int32_t *__r
   se = (red[0] + red[1]) + (red[2] + red[3]);
   const float lse = mx + __logf(se);
   const int tgt = targets[row];
+  if (tgt < 0 || tgt >= V) {  // ignored position: no loss, no gradient, nothing read out of bounds
+    if (threadIdx.x == 0) rowloss[row] = 0.f;
+    for (int c = threadIdx.x; c < V; c += 256) st<T>(zr + c, 0.f);
+    return;
+  }
   if (threadIdx.x == 0) rowloss[row] = lse - ld<T>(zr + tgt);
   __syncthreads();  // the target logit is read before anyone overwrites it
   for (int c = threadIdx.x; c < V; c += 256) {
@@ -61,6 +66,11 @@ __global__ __launch_bounds__(NT) void xent_rows_reg_kernel(bf16_t *z, const int3
   bf16_t *zr = z + (size_t)row * V;
   const int nvec = V >> 3;
   const int tgt = targets[row];
+  if (tgt < 0 || tgt >= V) {  // ignored position (uniform over the workgroup): zero loss, zero gradient
+    if (tid == 0) rowloss[row] = 0.f;
+    for (int v = tid; v < nvec; v += NT) *reinterpret_cast<uint4 *>(zr + v * 8) = uint4{0u, 0u, 0u, 0u};
+    return;
+  }
   const float ztgt = bf16_to_f32(zr[tgt]);  // read before any thread overwrites the row (barriers below)
   uint4 q[J];
   float mx = -INFINITY;

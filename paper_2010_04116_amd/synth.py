@@ -76,9 +76,13 @@ def block_shapes(w: Workload) -> Dict[str, Tuple[int, ...]]:
 def round_to_bf16(a: np.ndarray) -> np.ndarray:
     """float32 -> nearest bfloat16 (ties to even), returned as float32 values."""
     a = np.ascontiguousarray(a, dtype=np.float32)
-    u = a.view(np.uint32).astype(np.uint64)
-    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
-    return u.astype(np.uint32).view(np.float32).reshape(a.shape)
+    u = a.view(np.uint32)
+    r = u >> np.uint32(16)
+    r &= np.uint32(1)
+    r += np.uint32(0x7FFF)
+    r += u                      # finite inputs cannot carry out of 32 bits (|a| < 2^128 - 2^112)
+    r &= np.uint32(0xFFFF0000)
+    return r.view(np.float32).reshape(a.shape)
 
 
 def _rng(seed: int, *path: int) -> np.random.Generator:
@@ -122,13 +126,24 @@ def make_head_params(w: Workload, k: int, seed: int = PARAM_SEED) -> np.ndarray:
 
 def make_params(w: Workload, seed: int = PARAM_SEED, random_bias: bool = False,
                 random_ln: bool = False) -> dict:
-    """{'components': [[block dict]*L]*K, 'heads': [w_head]*K, 'head_blocks': [[block dict]*Lh]*K}."""
-    comps = [[make_block_params(w, k, l, seed, random_bias, random_ln)
-              for l in range(1, w.L + 1)] for k in range(1, w.K + 1)]
-    heads = [make_head_params(w, k, seed) for k in range(1, w.K + 1)]
+    """{'components': [[block dict]*L]*K, 'heads': [w_head]*K, 'head_blocks': [[block dict]*Lh]*K}.
+    Every tensor has a generator of its own (seed, component, block, tensor), so the draws do not
+    depend on the order they are made in: large workloads draw their blocks on a few threads."""
+    blk = lambda k, l: make_block_params(w, k, l, seed, random_bias, random_ln)
+    jobs = [(k, l) for k in range(1, w.K + 1) for l in range(1, w.L + 1)]
     # the blocks of head k are drawn like those of a component numbered 1000 + k
-    hblocks = [[make_block_params(w, 1000 + k, l, seed, random_bias, random_ln)
-                for l in range(1, w.Lh + 1)] for k in range(1, w.K + 1)]
+    hjobs = [(1000 + k, l) for k in range(1, w.K + 1) for l in range(1, w.Lh + 1)]
+    if (len(jobs) + len(hjobs)) * w.d * (4 * w.d + 2 * w.m) > 1 << 27:
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            out = list(ex.map(lambda kl: blk(*kl), jobs + hjobs))
+            heads = list(ex.map(lambda k: make_head_params(w, k, seed), range(1, w.K + 1)))
+    else:
+        out = [blk(k, l) for k, l in jobs + hjobs]
+        heads = [make_head_params(w, k, seed) for k in range(1, w.K + 1)]
+    comps = [out[(k - 1) * w.L:k * w.L] for k in range(1, w.K + 1)]
+    hout = out[len(jobs):]
+    hblocks = [hout[(k - 1) * w.Lh:k * w.Lh] for k in range(1, w.K + 1)]
     return {"components": comps, "heads": heads, "head_blocks": hblocks}
 
 

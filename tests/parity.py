@@ -3,18 +3,74 @@ seeded inputs and compare element by element.
 
 Tolerances (the benchmark spec): fp32 - relative error <= 1e-4 on every loss and on every
 gradient tensor; bf16 - <= 1e-3 on losses, <= 2e-2 on gradient tensors.  A loss is compared
-as |a-b|/|b|; a gradient tensor as ||a-b||_2/||b||_2 over the whole tensor."""
+as |a-b|/|b|; a gradient tensor as ||a-b||_2/||b||_2 over the whole tensor.
+
+A norm over a whole tensor can hide a wrong row, a dropped ragged-edge column or one bad
+tile, so every tensor is also held to three element-level bounds:
+  rows / cols  for every matrix, the L2 error of each row (column) relative to that row's
+               (column's) own norm, with the tensor's RMS row (column) norm as a floor so that
+               rows that are legitimately tiny are measured on the tensor's scale;
+  elem         max |a-b| / RMS(b): no single element may be off by more than a fraction of the
+               tensor's typical magnitude.
+A completely wrong row scores about 1 (or more) on `rows`, a zeroed tile 1 on both, a single
+garbage element >= 1 on `elem`; rounding noise scores a small multiple of the tensor tolerance
+(the bounds are ROW_FACTOR and ELEM_FACTOR times it: noise in a row of c elements scatters by
+about 1/sqrt(c) around the tensor figure, an extreme element of a Gaussian-like error
+distribution over 1e7 elements sits at 5-6 standard deviations).
+"""
+import json
+import os
+
 import numpy as np
 
 from oracle import interlock as O
 from paper_2010_04116_amd import binding, synth
 
 TOL = {"f32": dict(loss=1e-4, grad=1e-4), "bf16": dict(loss=1e-3, grad=2e-2)}
+ROW_FACTOR = 3.0      # rows / cols bound = ROW_FACTOR * tensor tolerance
+ELEM_FACTOR = 12.0    # elem bound = ELEM_FACTOR * tensor tolerance
+
+# observed margins of the run, by label: written to $IL_PARITY_MARGINS (a JSON file) when set
+MARGINS = {}
 
 
 def rel(a, b):
     nb = np.linalg.norm(b)
     return np.linalg.norm(np.asarray(a, np.float64) - b) / (nb if nb > 0 else 1.0)
+
+
+def elementwise(a, b):
+    """(tensor, rows, cols, elem) error figures of a against the reference b."""
+    a = np.asarray(a, np.float64)
+    b = np.asarray(b, np.float64)
+    diff = a - b
+    nb = np.linalg.norm(b)
+    out = {"tensor": np.linalg.norm(diff) / (nb if nb > 0 else 1.0)}
+    rms = nb / np.sqrt(b.size) if b.size else 0.0
+    out["elem"] = float(np.abs(diff).max() / rms) if rms > 0 else float(np.abs(diff).max())
+    if b.ndim == 2 and min(b.shape) > 1:
+        for name, axis in (("rows", 1), ("cols", 0)):
+            nref = np.sqrt((b * b).sum(axis=axis))
+            floor = np.sqrt((nref * nref).mean())
+            e = np.sqrt((diff * diff).sum(axis=axis)) / np.maximum(nref, floor if floor > 0 else 1.0)
+            out[name] = float(e.max())
+    return out
+
+
+def check_tensor(a, b, tol, what, worst, key):
+    if np.linalg.norm(b) == 0:
+        assert np.linalg.norm(a) == 0, f"{what}: expected exact zero"
+        return
+    assert np.all(np.isfinite(a)), f"{what}: non-finite values"
+    e = elementwise(a, b)
+    assert e["tensor"] <= tol, f"{what}: rel err {e['tensor']:.3e}"
+    for k in ("rows", "cols"):
+        if k in e:
+            assert e[k] <= ROW_FACTOR * tol, f"{what}: worst {k[:-1]} rel err {e[k]:.3e}"
+    assert e["elem"] <= ELEM_FACTOR * tol, f"{what}: max |a-b| / rms(b) = {e['elem']:.3e}"
+    for k, v in e.items():
+        kk = f"{key}.{k}"
+        worst[kk] = max(worst.get(kk, 0.0), float(v))
 
 
 def make_inputs(w, seed=0, random_bias=True, random_ln=True):
@@ -24,36 +80,47 @@ def make_inputs(w, seed=0, random_bias=True, random_ln=True):
     return params, x0, tgt
 
 
-def compare(w, got, ref, label=""):
+def compare(w, got, ref, label="", scale=1.0):
+    """Every loss, every component / head / head-block gradient tensor and dL/dx_0 of `got`
+    (the HIP path) against `ref` (the oracle).  `scale` multiplies the HIP path's gradients first
+    (the replicated-batch tests compare a batch of B copies with the oracle's single copy)."""
     tol = TOL[w.dtype]
     worst = {}
     for k in range(w.K):
         e = abs(got["losses"][k] - ref["losses"][k]) / abs(ref["losses"][k])
         assert e <= tol["loss"], f"{label} loss {k + 1}: rel err {e:.3e}"
-        worst["loss"] = max(worst.get("loss", 0), e)
+        worst["loss"] = max(worst.get("loss", 0), float(e))
         for l in range(w.L):
             for name in synth.BLOCK_TENSORS:
-                b = ref["comp_grads"][k][l][name]
-                a = got["comp_grads"][k][l][name]
-                if np.linalg.norm(b) == 0:
-                    assert np.linalg.norm(a) == 0, f"{label} c{k + 1} b{l + 1} {name}: expected exact zero"
-                    continue
-                e = rel(a, b)
-                assert e <= tol["grad"], f"{label} component {k + 1} block {l + 1} {name}: rel err {e:.3e}"
-                worst[name] = max(worst.get(name, 0), e)
-        e = rel(got["head_grads"][k], ref["head_grads"][k])
-        assert e <= tol["grad"], f"{label} head {k + 1}: rel err {e:.3e}"
-        worst["w_head"] = max(worst.get("w_head", 0), e)
+                check_tensor(got["comp_grads"][k][l][name] * scale, ref["comp_grads"][k][l][name], tol["grad"],
+                             f"{label} component {k + 1} block {l + 1} {name}", worst, name)
+        check_tensor(got["head_grads"][k] * scale, ref["head_grads"][k], tol["grad"], f"{label} head {k + 1}",
+                     worst, "w_head")
         for l in range(w.Lh):                                  # the head's own blocks
             for name in synth.BLOCK_TENSORS:
-                e = rel(got["head_block_grads"][k][l][name], ref["head_block_grads"][k][l][name])
-                assert e <= tol["grad"], f"{label} head {k + 1} block {l + 1} {name}: rel err {e:.3e}"
-                worst["head_" + name] = max(worst.get("head_" + name, 0), e)
+                check_tensor(got["head_block_grads"][k][l][name] * scale, ref["head_block_grads"][k][l][name],
+                             tol["grad"], f"{label} head {k + 1} block {l + 1} {name}", worst, "head_" + name)
     if np.linalg.norm(ref["dx0"]) > 0:
-        e = rel(got["dx0"], ref["dx0"])
-        assert e <= tol["grad"], f"{label} dx0: rel err {e:.3e}"
-        worst["dx0"] = e
+        check_tensor(got["dx0"] * scale, ref["dx0"], tol["grad"], f"{label} dx0", worst, "dx0")
+    record(label, w, worst)
     return worst
+
+
+def record(label, w, worst):
+    MARGINS[label or w.name] = dict(dtype=w.dtype, **{k: float(v) for k, v in worst.items()})
+    path = os.environ.get("IL_PARITY_MARGINS")
+    if path:
+        with open(path, "w") as f:
+            json.dump(MARGINS, f, indent=1, sort_keys=True)
+
+
+def summary(worst):
+    """One short line: the largest figure of each kind over all tensors."""
+    out = {}
+    for k, v in worst.items():
+        kind = k.rsplit(".", 1)[-1] if "." in k else k
+        out[kind] = max(out.get(kind, 0.0), v)
+    return " ".join(f"{k}={v:.2e}" for k, v in sorted(out.items()))
 
 
 def run_both(w, route="window_sum", seed=0, head_chunk=0, random_bias=True, random_ln=True):

@@ -15,7 +15,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_library_exports_every_declared_symbol():
     lib = binding.load()
-    hdr = open(os.path.join(ROOT, "include", "interlock.h")).read()
+    import glob
+    hdr = "".join(open(h).read() for h in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))))
     declared = set(re.findall(r"\b(il_[a-z_]+)\s*\(", hdr))
     assert {"il_init", "il_stage_forward", "il_head_xent", "il_stage_backward_nwise", "il_free"} <= declared
     for name in declared:

@@ -55,3 +55,29 @@ def test_without_microbatching():
     assert Tm.time_per_batch(4, 1, 9) == Tm.time_per_batch(4, 1, 4)        # the window is clamped to A
     with pytest.raises(ValueError):
         Tm.time_per_batch(0, 1, 1)
+
+
+def test_partial_window_branch_follows_the_appendix_derivation():
+    """App. C, Case 4 (M > 2, A < 2N - 1): every accelerator removed from the stack takes M - 2 slots
+    off the period, starting from the end-to-end period of an N-deep stack,
+        T(A, M, N) = (A - N)(M - 2) c(M) + 2 (M + N - 1) c(M),
+    and at A = 2N - 1 the branch meets the (N + 1) M c(M) of the deep-stack case.  The right-hand
+    sides are written from the derivation, not from the case formula the oracle evaluates."""
+    checked = 0
+    for N in range(3, 12):
+        for A in range(N + 1, 2 * N - 1):
+            for M in (3, 4, 5, 8, 16, 64):
+                c = Tm.C0 + Tm.C1 / M
+                want = (A - N) * (M - 2) * c + 2 * (M + N - 1) * c
+                assert math.isclose(Tm.time_per_batch(A, M, N), want, rel_tol=1e-13), (A, M, N)
+                # one accelerator fewer: exactly M - 2 slots less
+                step = Tm.time_per_batch(A, M, N) - Tm.time_per_batch(A - 1, M, N)
+                assert math.isclose(step, (M - 2) * c, rel_tol=1e-10), (A, M, N)
+                checked += 1
+        for M in (3, 4, 8, 16):
+            c = Tm.C0 + Tm.C1 / M
+            A = 2 * N - 1
+            below = (A - 1 - N) * (M - 2) * c + 2 * (M + N - 1) * c      # the derivation at A - 1
+            assert math.isclose(Tm.time_per_batch(A, M, N), (N + 1) * M * c, rel_tol=1e-13)
+            assert math.isclose(Tm.time_per_batch(A, M, N) - below, (M - 2) * c, rel_tol=1e-10)
+    assert checked > 100
