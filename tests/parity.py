@@ -10,13 +10,20 @@ tile, so every tensor is also held to three element-level bounds:
   rows / cols  for every matrix, the L2 error of each row (column) relative to that row's
                (column's) own norm, with the tensor's RMS row (column) norm as a floor so that
                rows that are legitimately tiny are measured on the tensor's scale;
-  elem         max |a-b| / RMS(b): no single element may be off by more than a fraction of the
-               tensor's typical magnitude.
+  elem         max |a-b| / (scale + |b|), scale = the largest of the RMS of the tensor, of the
+               element's row and of its column: no single element may be off by more than a fraction
+               of the typical magnitude around it or of its own magnitude.  (A head matrix's gradient
+               is near zero except in the columns of the target tokens, whose entries are sums of a
+               few x_r / N that are hundreds of times the tensor's RMS: the rounding of x to bf16 is
+               an error on THAT scale, which is why the column's RMS belongs to the yardstick.)
 A completely wrong row scores about 1 (or more) on `rows`, a zeroed tile 1 on both, a single
-garbage element >= 1 on `elem`; rounding noise scores a small multiple of the tensor tolerance
-(the bounds are ROW_FACTOR and ELEM_FACTOR times it: noise in a row of c elements scatters by
-about 1/sqrt(c) around the tensor figure, an extreme element of a Gaussian-like error
-distribution over 1e7 elements sits at 5-6 standard deviations).
+garbage or dropped element 0.5 or more on `elem`; rounding noise scores a small multiple of the tensor
+tolerance (the bounds are ROW_FACTOR and ELEM_FACTOR times it: the error of a row or column scatters
+around the tensor figure - measured: at most 1.4x for rows, 3x for columns - and an extreme element
+of a Gaussian-like error distribution over 1e7-1e8 elements sits at 5-6 standard deviations; measured
+worst over all fp32 cases 1e-5, over the bf16 cases 0.07 except for the head matrices' gradients, 0.13,
+and 0.16 for those in the replicated-batch runs, where the B copies of a sequence share their rounding
+errors instead of averaging them: the head's probabilities come from bf16-rounded logits).
 """
 import json
 import os
@@ -27,8 +34,8 @@ from oracle import interlock as O
 from paper_2010_04116_amd import binding, synth
 
 TOL = {"f32": dict(loss=1e-4, grad=1e-4), "bf16": dict(loss=1e-3, grad=2e-2)}
-ROW_FACTOR = 3.0      # rows / cols bound = ROW_FACTOR * tensor tolerance
-ELEM_FACTOR = 12.0    # elem bound = ELEM_FACTOR * tensor tolerance
+ROW_FACTOR = 4.0      # rows / cols bound = ROW_FACTOR * tensor tolerance  (bf16: 8e-2, fp32: 4e-4)
+ELEM_FACTOR = 6.0     # elem bound = ELEM_FACTOR * tensor tolerance         (bf16: 0.12, fp32: 6e-4)
 
 # observed margins of the run, by label: written to $IL_PARITY_MARGINS (a JSON file) when set
 MARGINS = {}
@@ -47,30 +54,48 @@ def elementwise(a, b):
     nb = np.linalg.norm(b)
     out = {"tensor": np.linalg.norm(diff) / (nb if nb > 0 else 1.0)}
     rms = nb / np.sqrt(b.size) if b.size else 0.0
-    out["elem"] = float(np.abs(diff).max() / rms) if rms > 0 else float(np.abs(diff).max())
+    scale = rms if rms > 0 else 1.0
     if b.ndim == 2 and min(b.shape) > 1:
+        b2 = b * b
         for name, axis in (("rows", 1), ("cols", 0)):
-            nref = np.sqrt((b * b).sum(axis=axis))
+            nref = np.sqrt(b2.sum(axis=axis))
             floor = np.sqrt((nref * nref).mean())
             e = np.sqrt((diff * diff).sum(axis=axis)) / np.maximum(nref, floor if floor > 0 else 1.0)
             out[name] = float(e.max())
+        rrms = np.sqrt(b2.mean(axis=1, keepdims=True))
+        crms = np.sqrt(b2.mean(axis=0, keepdims=True))
+        scale = np.maximum(np.maximum(rrms, crms), scale)
+    out["elem"] = float((np.abs(diff) / (scale + np.abs(b))).max())
     return out
 
 
-def check_tensor(a, b, tol, what, worst, key):
+def check_tensor(a, b, tol, what, worst, key, elem_factor=None):
+    """Holds a to the bounds; violations are collected in worst["violations"] (see assert_clean), so
+    that one run reports every tensor out of bounds, not only the first."""
+    bad = worst.setdefault("violations", [])
     if np.linalg.norm(b) == 0:
-        assert np.linalg.norm(a) == 0, f"{what}: expected exact zero"
+        if np.linalg.norm(a) != 0:
+            bad.append(f"{what}: expected exact zero")
         return
-    assert np.all(np.isfinite(a)), f"{what}: non-finite values"
+    if not np.all(np.isfinite(a)):
+        bad.append(f"{what}: non-finite values")
+        return
     e = elementwise(a, b)
-    assert e["tensor"] <= tol, f"{what}: rel err {e['tensor']:.3e}"
+    if e["tensor"] > tol:
+        bad.append(f"{what}: rel err {e['tensor']:.3e}")
     for k in ("rows", "cols"):
-        if k in e:
-            assert e[k] <= ROW_FACTOR * tol, f"{what}: worst {k[:-1]} rel err {e[k]:.3e}"
-    assert e["elem"] <= ELEM_FACTOR * tol, f"{what}: max |a-b| / rms(b) = {e['elem']:.3e}"
+        if k in e and e[k] > ROW_FACTOR * tol:
+            bad.append(f"{what}: worst {k[:-1]} rel err {e[k]:.3e}")
+    if e["elem"] > (elem_factor or ELEM_FACTOR) * tol:
+        bad.append(f"{what}: max |a-b| / (scale + |b|) = {e['elem']:.3e}")
     for k, v in e.items():
         kk = f"{key}.{k}"
         worst[kk] = max(worst.get(kk, 0.0), float(v))
+
+
+def assert_clean(worst, label=""):
+    bad = worst.pop("violations", [])
+    assert not bad, f"{label}: {len(bad)} bound(s) exceeded:\n  " + "\n  ".join(bad[:40])
 
 
 def make_inputs(w, seed=0, random_bias=True, random_ln=True):
@@ -80,29 +105,33 @@ def make_inputs(w, seed=0, random_bias=True, random_ln=True):
     return params, x0, tgt
 
 
-def compare(w, got, ref, label="", scale=1.0):
+def compare(w, got, ref, label="", scale=1.0, head_elem_factor=None):
     """Every loss, every component / head / head-block gradient tensor and dL/dx_0 of `got`
     (the HIP path) against `ref` (the oracle).  `scale` multiplies the HIP path's gradients first
-    (the replicated-batch tests compare a batch of B copies with the oracle's single copy)."""
+    (the ignored-target test compares half a batch with the oracle's whole one);
+    `head_elem_factor` replaces ELEM_FACTOR for the head matrices' gradients (replicated-batch runs)."""
     tol = TOL[w.dtype]
     worst = {}
     for k in range(w.K):
         e = abs(got["losses"][k] - ref["losses"][k]) / abs(ref["losses"][k])
-        assert e <= tol["loss"], f"{label} loss {k + 1}: rel err {e:.3e}"
+        if not e <= tol["loss"]:
+            worst.setdefault("violations", []).append(f"{label} loss {k + 1}: rel err {e:.3e}")
         worst["loss"] = max(worst.get("loss", 0), float(e))
         for l in range(w.L):
             for name in synth.BLOCK_TENSORS:
                 check_tensor(got["comp_grads"][k][l][name] * scale, ref["comp_grads"][k][l][name], tol["grad"],
                              f"{label} component {k + 1} block {l + 1} {name}", worst, name)
         check_tensor(got["head_grads"][k] * scale, ref["head_grads"][k], tol["grad"], f"{label} head {k + 1}",
-                     worst, "w_head")
+                     worst, "w_head", head_elem_factor)
         for l in range(w.Lh):                                  # the head's own blocks
             for name in synth.BLOCK_TENSORS:
                 check_tensor(got["head_block_grads"][k][l][name] * scale, ref["head_block_grads"][k][l][name],
                              tol["grad"], f"{label} head {k + 1} block {l + 1} {name}", worst, "head_" + name)
     if np.linalg.norm(ref["dx0"]) > 0:
         check_tensor(got["dx0"] * scale, ref["dx0"], tol["grad"], f"{label} dx0", worst, "dx0")
-    record(label, w, worst)
+    bad = worst.get("violations", [])
+    record(label, w, {k: v for k, v in worst.items() if k != "violations"})
+    assert_clean(worst, label)
     return worst
 
 

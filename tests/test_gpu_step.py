@@ -6,7 +6,7 @@ import pytest
 
 from oracle import interlock as O
 from paper_2010_04116_amd import binding, synth
-from parity import compare, make_inputs, run_both, summary, check_tensor, record, TOL
+from parity import compare, make_inputs, run_both, summary, check_tensor, record, assert_clean, TOL
 
 pytestmark = pytest.mark.gpu
 TINY = synth.WORKLOADS["tiny"]
@@ -438,8 +438,10 @@ def _full_size(name, seed, n=None):
     assert np.all(np.isfinite(got["losses"])) and np.all(got["losses"] > np.log(w.V) - 0.5)
     for k in range(w.K):
         np.testing.assert_allclose(got["head_grads"][k].sum(axis=1), 0, atol=2e-3)   # sum_v dlogits = 0
+    bad = worst.pop("violations", [])
     record(label + " (distinct, sequence 0)", w, worst)
     say("distinct:", summary(worst))
+    assert_clean({"violations": bad}, label + " (distinct)")
     # (2)
     for t in range(1, w.B):              # the replicas come out alike (same tiles, other row blocks)
         assert np.array_equal(rep["x"][w.K][t * w.T:(t + 1) * w.T], rep["x"][w.K][:w.T]), f"{label}: replica {t}"
