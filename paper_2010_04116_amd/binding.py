@@ -24,7 +24,8 @@ ROUTES = {"window_sum": 0, "far_head": 1, "mean_local_far": 2}
 SYMBOLS = ("il_init", "il_stage_forward", "il_head_xent", "il_stage_backward_nwise", "il_free",
            "il_routing_plan", "il_profile_read", "il_status_string", "il_test_gemm", "il_lr_schedule",
            "il_adam_step", "il_embed_forward", "il_embed_backward", "il_set_accumulation",
-           "il_time_per_batch", "il_optimal_microbatches", "il_measure_mfma_peak", "il_measure_copy_peak")
+           "il_time_per_batch", "il_optimal_microbatches", "il_measure_mfma_peak", "il_measure_copy_peak",
+           "il_head_xent_static")
 
 
 class il_config(C.Structure):
@@ -57,6 +58,7 @@ def load():
     lib.il_init.argtypes = [C.POINTER(il_config), C.POINTER(vp)]
     lib.il_stage_forward.argtypes = [vp, i32, vp, vp]
     lib.il_head_xent.argtypes = [vp, i32, vp, vp, vp]
+    lib.il_head_xent_static.argtypes = [vp, i32, vp, vp, vp]
     lib.il_stage_backward_nwise.argtypes = [vp, i32, vp]
     lib.il_free.argtypes = [vp]
     lib.il_routing_plan.argtypes = [i32, i32, i32, C.POINTER(i32), C.POINTER(i32)]
@@ -148,6 +150,11 @@ def il_stage_forward(ctx, k: int, x_in, x_out):
 def il_head_xent(ctx, k: int, x_k, targets, loss_out):
     _check(load().il_head_xent(ctx, k, x_k.data_ptr(), targets.data_ptr(), loss_out.data_ptr()),
            f"il_head_xent({k})")
+
+
+def il_head_xent_static(ctx, k: int, x_k, targets, loss_out):
+    _check(load().il_head_xent_static(ctx, k, x_k.data_ptr(), targets.data_ptr(), loss_out.data_ptr()),
+           f"il_head_xent_static({k})")
 
 
 def il_stage_backward_nwise(ctx, k: int, dx0_out=None):
@@ -347,11 +354,12 @@ class Step:
         self.x[0].copy_(t.from_numpy(np.ascontiguousarray(x0, dtype=np.float32)))
         self.targets.copy_(t.from_numpy(np.ascontiguousarray(targets.reshape(-1), dtype=np.int32)))
 
-    def run(self):
+    def run(self, static_heads: bool = False):
         w = self.w
+        head = il_head_xent_static if static_heads else il_head_xent
         for k in range(1, w.K + 1):
             il_stage_forward(self.ctx, k, self.x[k - 1], self.x[k])
-            il_head_xent(self.ctx, k, self.x[k], self.targets, self.losses[k - 1:])
+            head(self.ctx, k, self.x[k], self.targets, self.losses[k - 1:])
         for k in range(w.K, 0, -1):
             il_stage_backward_nwise(self.ctx, k, self.dx0 if k == 1 else None)
 

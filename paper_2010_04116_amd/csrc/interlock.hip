@@ -12,6 +12,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -786,7 +787,8 @@ int il_stage_forward(il_ctx *c, int32_t k, const float *x_in, float *x_out) {
 }
 
 // The head's scratch: the bf16 / fp32 copy of its input, one logits tile, per-row losses and the
-// split-K partial products of dx.  il_head_xent takes it from the caller's workspace.
+// split-K partial products of dx.  il_head_xent takes it from the caller's workspace,
+// il_head_xent_static from the library's static device array.
 struct HeadScratch {
   char *xb, *Z; float *rowloss, *skws; size_t skws_floats;
 };
@@ -912,6 +914,49 @@ int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets,
   if (!c) return IL_E_ARG;
   const HeadScratch hs{c->xb, c->Z, c->rowloss, c->skws, c->skws_floats};
   return head_xent_impl(c, k, x_k, targets, loss_out, hs, false);
+}
+
+// ---- the head without a workspace of its own -------------------------------------------------
+// The library's static scratch: every GPU the library runs on holds its own copy of this array at
+// its own address until the process ends.  Host code never passes the array's name to a kernel (on
+// the host it is a stand-in, not a device address): the address is looked up once per device.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// The current device's copy of `scratch` (looked up on the first call on that device).
+int static_scratch(char **out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return IL_E_HIP;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return IL_E_HIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = (char *)g_scratch_ptr[dev];
+  return IL_OK;
+}
+}  // namespace
+
+int il_head_xent_static(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets, float *loss_out) {
+  if (!c) return IL_E_ARG;
+  if (c->Lh > 0) return IL_E_SHAPE;  // heads with blocks of their own need the workspace's saved activations
+  // the four pieces the head's kernels use, carved from the static array (256-byte aligned pieces)
+  Carver cv(nullptr);
+  const size_t o_xb = cv.off; cv.take((size_t)c->N * c->d * c->eb);
+  const size_t o_z = cv.off; cv.take((size_t)c->Nc * c->V * c->eb);
+  const size_t o_rl = cv.off; cv.take((size_t)c->N * 4);
+  const size_t o_sk = cv.off; cv.take(c->skws_floats * 4);
+  if (cv.off > kStaticScratchBytes) return IL_E_WORKSPACE;
+  char *base = nullptr;
+  { const int rc = static_scratch(&base); if (rc) return rc; }
+  const HeadScratch hs{base + o_xb, base + o_z, (float *)(base + o_rl), (float *)(base + o_sk), c->skws_floats};
+  return head_xent_impl(c, k, x_k, targets, loss_out, hs, true);
 }
 
 int il_stage_backward_nwise(il_ctx *c, int32_t k, float *dx0_out) {
