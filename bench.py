@@ -33,6 +33,7 @@ PEAK_HBM_GBS = 8000.0
 # carried here for the workloads they were measured on and are null for any other.
 MEASURED_TRAFFIC = {
     "small_bf16_n2": 41.88e6,   # 32.18 MB read + 9.70 MB written per launch, 768 launches
+    "large_bf16_n2": 479.27e6,  # 390.89 MB read + 88.39 MB written per launch, 3240 launches
 }
 
 # which roofline bounds a kernel class, and the peak its fraction is taken against
@@ -345,6 +346,8 @@ def main():
                          "name:n overrides the window, e.g. large:6")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-peaks", action="store_true", help="skip the MFMA-only / streaming-copy micro-benchmarks")
+    ap.add_argument("--peaks-only", action="store_true",
+                    help="run only the MFMA-only / streaming-copy micro-benchmarks and print their JSON line")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="first run two launches of the library's streaming copy kernel over this many MiB "
                          "(a kernel of known HBM traffic, against which rocprofv3's FETCH_SIZE / WRITE_SIZE "
@@ -365,6 +368,10 @@ def main():
                                      stream=torch.cuda.current_stream().cuda_stream)
         del src, dst
     peaks = None if a.no_peaks else measured_peaks()
+    if a.peaks_only:
+        print(json.dumps({"measured_peaks": peaks, "nominal": {"bf16_mfma_tflops": PEAK_BF16_TFLOPS,
+                                                                "hbm_gbs": PEAK_HBM_GBS}}))
+        return
     w = synth.WORKLOADS[a.workload]
     if a.n:
         w = w.with_(n=a.n)
