@@ -42,22 +42,25 @@ template <typename T> __device__ inline void st(T *p, float v);
 template <> __device__ inline void st<float>(float *p, float v) { *p = v; }
 template <> __device__ inline void st<bf16_t>(bf16_t *p, float v) { *p = f32_to_bf16(v); }
 
-// tanh-form GELU and its derivative, fp32.  tanh(y) = 1 - 2/(exp(2y)+1) through the hardware
-// exp2 and reciprocal (relative error ~1e-6, far inside the fp32 tolerance; saturates correctly
-// for large |y|): the library tanhf costs several times more and sat in every MLP epilogue.
-__device__ inline float tanh_fast(float y) {
-  const float e = __builtin_amdgcn_exp2f(y * 2.8853900817779268f);  // exp(2y)
-  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(e + 1.0f);
+// tanh-form GELU and its derivative, fp32, written through the logistic function: with
+// y = sqrt(2/pi) (u + 0.044715 u^3) and s = 1 / (1 + exp(-2y)), tanh(y) = 2s - 1, so
+//   gelu(u)  = u s,      gelu'(u) = s + s (1 - s) * 2 sqrt(2/pi) u (1 + 3 * 0.044715 u^2).
+// exp and the reciprocal are the hardware instructions (relative error ~1e-6, far inside the fp32
+// tolerance; both ends saturate correctly: s -> 0 or 1).  These sit in the epilogue of every MLP GEMM,
+// where the two wavefronts of a SIMD share one vector ALU: the derivative costs eight plain and two
+// transcendental instructions per element in this form.
+__device__ inline float gelu_sigmoid(float u, float u2) {
+  const float y = u * __builtin_fmaf(0.044715f, u2, 1.0f);
+  const float e = __builtin_amdgcn_exp2f(y * -2.3022081715f);  // exp(-2 sqrt(2/pi) y'), -2 * 0.79788456 * log2(e)
+  return __builtin_amdgcn_rcpf(e + 1.0f);
 }
-__device__ inline float gelu_f(float u) {
-  const float c = 0.7978845608028654f;
-  const float t = tanh_fast(c * (u + 0.044715f * u * u * u));
-  return 0.5f * u * (1.0f + t);
-}
+__device__ inline float gelu_f(float u) { return u * gelu_sigmoid(u, u * u); }
 __device__ inline float gelu_grad_f(float u) {
-  const float c = 0.7978845608028654f;
-  const float t = tanh_fast(c * (u + 0.044715f * u * u * u));
-  return 0.5f * (1.0f + t) + 0.5f * u * (1.0f - t * t) * c * (1.0f + 0.134145f * u * u);
+  const float u2 = u * u;
+  const float s = gelu_sigmoid(u, u2);
+  const float w = u * __builtin_fmaf(0.2140644488f, u2, 1.5957691216f);  // 2 sqrt(2/pi) u (1 + 0.134145 u^2)
+  const float t = __builtin_fmaf(-w, s, w);                              // w (1 - s)
+  return __builtin_fmaf(s, t, s);
 }
 
 // Up to 16 gradient streams are stacked along the row dimension of the backward
