@@ -387,22 +387,29 @@ __device__ __forceinline__ void attn_bwd_dq_body(const bf16_t *__restrict__ qkv,
 }
 
 // ------------------------------------------------------------------ backward: dK, dV ----
-// grid (ceil(T/128), B*H, streams); 4 wavefronts, each owns 32 keys (a lane owns one key
-// column); query tiles of 64 from the diagonal to the end of the sequence.  Scores are
-// computed as S = Q K^T with the query index in the accumulator rows, so P and dS feed the
-// products dV^T = dO^T P and dK^T = Q^T dS directly from registers.
-template <int DH>
+// grid (ceil(T/128), B*H, streams) - or streams * 2 for the split form; 4 wavefronts, each owns
+// 32 keys (a lane owns one key column); query tiles of 64 from the diagonal to the end of the
+// sequence.  Scores are computed as S = Q K^T with the query index in the accumulator rows, so P
+// and dS feed the products dV^T = dO^T P and dK^T = Q^T dS directly from registers.
+// WHAT: 0 = dK and dV in one pass; 1 = dV only; 2 = dK only.  At head width 128 the one-pass form
+// holds 64 registers of K / V fragments and 128 of accumulators: it does not fit the 256
+// architectural registers, runs one wavefront per SIMD and pays accumulation-register moves.  Split
+// into a dV pass (K fragments, 64 accumulator registers) and a dK pass (K and V fragments, 64
+// accumulator registers), both fit with two wavefronts per SIMD; the score product is computed in
+// both (40 matrix instructions per 32x32 sub-tile instead of 32), which the kernel - bound by
+// latency, not by the matrix unit - more than wins back.
+template <int DH, int WHAT>
 __device__ __forceinline__ void attn_bwd_dkv_body(const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ d_o,
                                                   const float *__restrict__ lse, const float *__restrict__ dsum, int B,
-                                                  int T, int H, bf16_t *__restrict__ dqkv) {
+                                                  int T, int H, int sidx, bf16_t *__restrict__ dqkv, char *smem) {
+  constexpr bool DO_DV = WHAT != 2, DO_DK = WHAT != 1;
   constexpr int BKV = 128, BQ = 64;
   constexpr int QT = BQ * DH * 2;                 // one staged tile
-  constexpr int STAGE = 2 * QT + 2 * BQ * 4;      // Q, dO as stored, lse, dsum
+  constexpr int STAGE = 2 * QT + 2 * BQ * 4;      // Q, dO as stored, lse, dsum; smem holds two stages
   typedef TokTile<BQ, DH> Tile;
-  __shared__ __attribute__((aligned(16))) char smem[2 * STAGE];
   const int t = threadIdx.x, lane = t & 63, hh = lane >> 5, lk_ = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int b = blockIdx.y / H, h = blockIdx.y % H, sidx = blockIdx.z;
+  const int b = blockIdx.y / H, h = blockIdx.y % H;
   const int d = H * DH;
   const size_t ld3 = 3 * (size_t)d, N = (size_t)B * T;
   const bf16_t *qbase = qkv + (size_t)b * T * ld3 + h * DH;
@@ -413,22 +420,25 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const bf16_t *__restrict__ qkv
   const int kv0 = blockIdx.x * BKV, kvw0 = kv0 + 32 * wave, kv = kvw0 + lk_;
   const int qt0 = kv0 / BQ, nqt = (T + BQ - 1) / BQ;
 
-  Frag kf[DH / 16], vf[DH / 16];
+  Frag kf[DH / 16], vf[DO_DK ? DH / 16 : 1];
 #pragma unroll
   for (int ks = 0; ks < DH / 16; ++ks) {
     if (kv < T) {
       kf[ks].q = ldg16(kbase + (size_t)kv * ld3 + 16 * ks + 8 * hh);
-      vf[ks].q = ldg16(vbase + (size_t)kv * ld3 + 16 * ks + 8 * hh);
+      if constexpr (DO_DK) vf[ks].q = ldg16(vbase + (size_t)kv * ld3 + 16 * ks + 8 * hh);
     } else {
       kf[ks].q = make_uint4(0, 0, 0, 0);
-      vf[ks].q = make_uint4(0, 0, 0, 0);
+      if constexpr (DO_DK) vf[ks].q = make_uint4(0, 0, 0, 0);
     }
   }
-  floatx16 dk[DH / 32], dv[DH / 32];
+  floatx16 dk[DO_DK ? DH / 32 : 1], dv[DO_DV ? DH / 32 : 1];
 #pragma unroll
   for (int i = 0; i < DH / 32; ++i)
 #pragma unroll
-    for (int r = 0; r < 16; ++r) { dk[i][r] = 0.f; dv[i][r] = 0.f; }
+    for (int r = 0; r < 16; ++r) {
+      if constexpr (DO_DK) dk[i][r] = 0.f;
+      if constexpr (DO_DV) dv[i][r] = 0.f;
+    }
   const float sc = rsqrtf((float)DH);
   const float sc2 = sc * kLog2e;
 
@@ -443,7 +453,7 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const bf16_t *__restrict__ qkv
     lq.issue(rq, base, wave, r0, T);
     lg.issue(rg, base + QT, wave, r0, T);
     if (wave == 0) dma4(rl, lds_address(base + 2 * QT), (uint32_t)(r0 + lane) * 4u);
-    if (wave == 1) dma4(rd, lds_address(base + 2 * QT + BQ * 4), (uint32_t)(r0 + lane) * 4u);
+    if (DO_DK && wave == 1) dma4(rd, lds_address(base + 2 * QT + BQ * 4), (uint32_t)(r0 + lane) * 4u);
   };
   if (qt0 < nqt) issue(qt0, smem);
 
@@ -463,9 +473,11 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const bf16_t *__restrict__ qkv
 #pragma unroll
       for (int ks = 0; ks < DH / 16; ++ks) {
         const bf16x8 qf = Tile::rowfrag(sq, 32 * a, ks, lane);
-        const bf16x8 gf = Tile::rowfrag(sg, 32 * a, ks, lane);
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf, kf[ks].v, s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf, vf[ks].v, dp, 0, 0, 0);
+        if constexpr (DO_DK) {
+          const bf16x8 gf = Tile::rowfrag(sg, 32 * a, ks, lane);
+          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gf, vf[ks].v, dp, 0, 0, 0);
+        }
       }
       const bool diag = qa0 < kvw0 + 31 || qa0 + 32 > T;
       Frag pf[2], sf[2];  // P and dS of the sub-tile, packed to bf16 as they are produced
@@ -473,8 +485,12 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const bf16_t *__restrict__ qkv
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const float4 l4 = *reinterpret_cast<const float4 *>(sl + 32 * a + 8 * g + 4 * hh);
-          const float4 d4 = *reinterpret_cast<const float4 *>(sd + 32 * a + 8 * g + 4 * hh);
-          const float lv4[4] = {l4.x, l4.y, l4.z, l4.w}, dv4[4] = {d4.x, d4.y, d4.z, d4.w};
+          const float lv4[4] = {l4.x, l4.y, l4.z, l4.w};
+          float dv4[4] = {0.f, 0.f, 0.f, 0.f};
+          if constexpr (DO_DK) {
+            const float4 d4 = *reinterpret_cast<const float4 *>(sd + 32 * a + 8 * g + 4 * hh);
+            dv4[0] = d4.x; dv4[1] = d4.y; dv4[2] = d4.z; dv4[3] = d4.w;
+          }
           float p4[4], s4[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
@@ -487,10 +503,14 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const bf16_t *__restrict__ qkv
             p4[e] = p;
             s4[e] = p * (dp[r] - dv4[e]) * sc;  // dS
           }
-          pf[g >> 1].u[2 * (g & 1)] = pack2(p4[0], p4[1]);
-          pf[g >> 1].u[2 * (g & 1) + 1] = pack2(p4[2], p4[3]);
-          sf[g >> 1].u[2 * (g & 1)] = pack2(s4[0], s4[1]);
-          sf[g >> 1].u[2 * (g & 1) + 1] = pack2(s4[2], s4[3]);
+          if constexpr (DO_DV) {
+            pf[g >> 1].u[2 * (g & 1)] = pack2(p4[0], p4[1]);
+            pf[g >> 1].u[2 * (g & 1) + 1] = pack2(p4[2], p4[3]);
+          }
+          if constexpr (DO_DK) {
+            sf[g >> 1].u[2 * (g & 1)] = pack2(s4[0], s4[1]);
+            sf[g >> 1].u[2 * (g & 1) + 1] = pack2(s4[2], s4[3]);
+          }
         }
       };
       if (DH > 128 || diag)
@@ -501,10 +521,14 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const bf16_t *__restrict__ qkv
       for (int bq = 0; bq < 2; ++bq) {
 #pragma unroll
         for (int dt = 0; dt < DH / 32; ++dt) {
-          const bf16x8 gt = Tile::trfrag(sg, 32 * a + 16 * bq, dt, lane);
-          const bf16x8 qtf = Tile::trfrag(sq, 32 * a + 16 * bq, dt, lane);
-          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, pf[bq].v, dv[dt], 0, 0, 0);
-          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qtf, sf[bq].v, dk[dt], 0, 0, 0);
+          if constexpr (DO_DV) {
+            const bf16x8 gt = Tile::trfrag(sg, 32 * a + 16 * bq, dt, lane);
+            dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(gt, pf[bq].v, dv[dt], 0, 0, 0);
+          }
+          if constexpr (DO_DK) {
+            const bf16x8 qtf = Tile::trfrag(sq, 32 * a + 16 * bq, dt, lane);
+            dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qtf, sf[bq].v, dk[dt], 0, 0, 0);
+          }
         }
       }
     }
@@ -516,12 +540,16 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const bf16_t *__restrict__ qkv
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         uint2 v;
-        v.x = pack2(dk[dt][4 * g], dk[dt][4 * g + 1]);
-        v.y = pack2(dk[dt][4 * g + 2], dk[dt][4 * g + 3]);
-        *reinterpret_cast<uint2 *>(kp + dt * 32 + 8 * g + 4 * hh) = v;
-        v.x = pack2(dv[dt][4 * g], dv[dt][4 * g + 1]);
-        v.y = pack2(dv[dt][4 * g + 2], dv[dt][4 * g + 3]);
-        *reinterpret_cast<uint2 *>(kp + d + dt * 32 + 8 * g + 4 * hh) = v;
+        if constexpr (DO_DK) {
+          v.x = pack2(dk[dt][4 * g], dk[dt][4 * g + 1]);
+          v.y = pack2(dk[dt][4 * g + 2], dk[dt][4 * g + 3]);
+          *reinterpret_cast<uint2 *>(kp + dt * 32 + 8 * g + 4 * hh) = v;
+        }
+        if constexpr (DO_DV) {
+          v.x = pack2(dv[dt][4 * g], dv[dt][4 * g + 1]);
+          v.y = pack2(dv[dt][4 * g + 2], dv[dt][4 * g + 3]);
+          *reinterpret_cast<uint2 *>(kp + d + dt * 32 + 8 * g + 4 * hh) = v;
+        }
       }
   }
 }
@@ -549,13 +577,27 @@ __global__ __launch_bounds__(256) void attn_bwd_dkv_mfma(const bf16_t *__restric
                                                          const float *__restrict__ lse,
                                                          const float *__restrict__ dsum, int B, int T, int H,
                                                          bf16_t *__restrict__ dqkv) {
-  attn_bwd_dkv_body<DH>(qkv, d_o, lse, dsum, B, T, H, dqkv);
+  __shared__ __attribute__((aligned(16))) char smem[2 * (2 * 64 * DH * 2 + 2 * 64 * 4)];
+  attn_bwd_dkv_body<DH, 0>(qkv, d_o, lse, dsum, B, T, H, blockIdx.z, dqkv, smem);
 }
 template <int DH>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void attn_bwd_dkv_mfma_v(
     const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ d_o, const float *__restrict__ lse,
     const float *__restrict__ dsum, int B, int T, int H, bf16_t *__restrict__ dqkv) {
-  attn_bwd_dkv_body<DH>(qkv, d_o, lse, dsum, B, T, H, dqkv);
+  __shared__ __attribute__((aligned(16))) char smem[2 * (2 * 64 * DH * 2 + 2 * 64 * 4)];
+  attn_bwd_dkv_body<DH, 0>(qkv, d_o, lse, dsum, B, T, H, blockIdx.z, dqkv, smem);
+}
+// The split form: grid.z = 2 * streams; even z computes dK of stream z / 2 (the longer pass, dispatched
+// first), odd z its dV.
+template <int DH>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void attn_bwd_dkv_split_mfma(
+    const bf16_t *__restrict__ qkv, const bf16_t *__restrict__ d_o, const float *__restrict__ lse,
+    const float *__restrict__ dsum, int B, int T, int H, bf16_t *__restrict__ dqkv) {
+  __shared__ __attribute__((aligned(16))) char smem[2 * (2 * 64 * DH * 2 + 2 * 64 * 4)];
+  if (blockIdx.z & 1)
+    attn_bwd_dkv_body<DH, 1>(qkv, d_o, lse, dsum, B, T, H, blockIdx.z >> 1, dqkv, smem);
+  else
+    attn_bwd_dkv_body<DH, 2>(qkv, d_o, lse, dsum, B, T, H, blockIdx.z >> 1, dqkv, smem);
 }
 
 }  // namespace
@@ -585,8 +627,8 @@ hipError_t attention_backward_mfma(const void *qkv, const void *o, const void *d
   } else if (dh == 128) {
     hipLaunchKernelGGL(attn_bwd_dq_mfma_v<128>, grid, dim3(256), 0, s, (const bf16_t *)qkv, (const bf16_t *)o,
                        (const bf16_t *)d_o, lse, B, T, H, (bf16_t *)dqkv, dsum);
-    hipLaunchKernelGGL(attn_bwd_dkv_mfma<128>, grid, dim3(256), 0, s, (const bf16_t *)qkv, (const bf16_t *)d_o, lse,
-                       dsum, B, T, H, (bf16_t *)dqkv);
+    hipLaunchKernelGGL(attn_bwd_dkv_split_mfma<128>, dim3(grid.x, grid.y, 2 * ns), dim3(256), 0, s, (const bf16_t *)qkv,
+                       (const bf16_t *)d_o, lse, dsum, B, T, H, (bf16_t *)dqkv);
   } else if (dh == 256) {
     hipLaunchKernelGGL(attn_bwd_dq_mfma<256>, grid, dim3(256), 0, s, (const bf16_t *)qkv, (const bf16_t *)o,
                        (const bf16_t *)d_o, lse, B, T, H, (bf16_t *)dqkv, dsum);

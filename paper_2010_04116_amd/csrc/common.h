@@ -35,6 +35,17 @@ __device__ inline uint32_t pack_bf16x2(float a, float b) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
+// IEEE half <-> float (hardware conversions)
+__device__ inline float f16_to_f32(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+__device__ inline uint32_t pack_f16x2(float a, float b) {  // a in the low half; round to nearest even, clamped to the finite range
+  const float lim = 65504.f;
+  typedef __attribute__((__vector_size__(2 * sizeof(_Float16)))) _Float16 f16x2_t;
+  f16x2_t v;
+  v[0] = (_Float16)fminf(fmaxf(a, -lim), lim);
+  v[1] = (_Float16)fminf(fmaxf(b, -lim), lim);
+  return __builtin_bit_cast(uint32_t, v);
+}
+
 template <typename T> __device__ inline float ld(const T *p);
 template <> __device__ inline float ld<float>(const float *p) { return *p; }
 template <> __device__ inline float ld<bf16_t>(const bf16_t *p) { return bf16_to_f32(*p); }
@@ -78,7 +89,9 @@ enum Epi {
   EPI_BIAS_RES = 3,   // Cf = acc + bias + res[row, col]          (fp32 out, fp32 residual)
   EPI_GELU_BWD = 4,   // C = acc * gelu'(aux[row mod wrap, col])  (T out, T aux)
   EPI_STORE_F32 = 5,  // Cf = acc                                 (fp32 out)
-  EPI_WGRAD = 6       // Cf = scale*acc (+ Cf if beta)            (fp32 out)
+  EPI_WGRAD = 6,      // Cf = scale*acc (+ Cf if beta)            (fp32 out)
+  EPI_STORE_F16 = 7   // C = acc as IEEE half, clamped to +-65504 (bf16 operands only): the head's logits tile,
+                      // whose softmax wants the three extra mantissa bits and never the range
 };
 
 struct GemmArgs {
@@ -179,8 +192,9 @@ hipError_t attention_backward(int dtype, const void *qkv, const void *o, const v
 // ---- cross-entropy rows (xent.hip) --------------------------------------------------------
 // For each of `rows` logit rows z (T, [rows, V], in place): rowloss = lse - z[target];
 // z <- (softmax(z) - onehot(target)) * inv_n.
+// bf16 mode: with z_is_f16 the logits arrive as IEEE half (EPI_STORE_F16); dlogits leave as bf16 either way.
 hipError_t xent_rows(int dtype, void *z, const int32_t *targets, int rows, int V, float inv_n,
-                     float *rowloss, hipStream_t s);
+                     float *rowloss, hipStream_t s, int z_is_f16 = 0);
 // loss_out[0] = scale * sum(rowloss[0..rows))
 hipError_t sum_scalar(const float *rowloss, int rows, float scale, float *loss_out, hipStream_t s);
 

@@ -57,6 +57,11 @@ __device__ inline void emit8(const GemmArgs &g, float4 v0, float4 v1, int grow, 
   const size_t o = (size_t)grow * g.ldc + gcol;
   if constexpr (EPI == EPI_STORE) {
     *reinterpret_cast<u32x4 *>((bf16_t *)g.C + o) = pack8(v);
+  } else if constexpr (EPI == EPI_STORE_F16) {
+    u32x4 h;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) h[i] = pack_f16x2(v[2 * i], v[2 * i + 1]);
+    *reinterpret_cast<u32x4 *>((uint16_t *)g.C + o) = h;
   } else if constexpr (EPI == EPI_BIAS) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] += bv[e];
@@ -709,6 +714,7 @@ hipError_t gemm_bf16_batch(const GemmArgs *list, int count, hipStream_t s) {
     case 1:  // activations x weights[K,N]: forward linears, head logits
       switch (g.epi) {
         case EPI_STORE: return pick_tile<false, true, EPI_STORE>(b, s);
+        case EPI_STORE_F16: return pick_tile<false, true, EPI_STORE_F16>(b, s);
         case EPI_BIAS: return pick_tile<false, true, EPI_BIAS>(b, s);
         case EPI_BIAS_GELU: return pick_tile<false, true, EPI_BIAS_GELU>(b, s);
         case EPI_BIAS_RES: return pick_tile<false, true, EPI_BIAS_RES>(b, s);

@@ -837,14 +837,17 @@ static int head_xent_impl(il_ctx *c, int32_t k, const float *x_k, const int32_t 
     GemmArgs g = base_args();  // logits tile z = x W_h
     g.A = xc; g.lda = d; g.a_kmajor = 0;
     g.B = P(c, c->hoff[k - 1]); g.ldb = V; g.b_kmajor = 1;
-    g.M = rows; g.N = V; g.K = d; g.epi = EPI_STORE; g.C = hs.Z; g.ldc = V;
+    // bf16 mode: the tile holds the logits as IEEE half (three more mantissa bits for the softmax's
+    // exponentials) whenever the in-register cross-entropy kernel can take the row
+    const bool zf16 = dt == IL_BF16 && V <= 65536;
+    g.M = rows; g.N = V; g.K = d; g.epi = zf16 ? EPI_STORE_F16 : EPI_STORE; g.C = hs.Z; g.ldc = V;
     {
       Scope sc(c, KC_GEMM_HEAD, 2.0 * rows * V * d, gemm_bytes(c, g));
       IL_TRY(gemm(c, g));
     }
     {
       Scope sc(c, KC_XENT, 0, 2.0 * rows * V * eb);
-      IL_TRY(xent_rows(dt, hs.Z, targets + r0, rows, V, c->grad_scale / N, hs.rowloss + r0, c->stream));
+      IL_TRY(xent_rows(dt, hs.Z, targets + r0, rows, V, c->grad_scale / N, hs.rowloss + r0, c->stream, zf16));
     }
     g = base_args();  // dx = dz W_h^T
     g.A = hs.Z; g.lda = V; g.a_kmajor = 0;
@@ -1044,7 +1047,8 @@ int il_test_gemm(int32_t dtype, const void *A, const void *B, int32_t M, int32_t
                  int32_t beta, int32_t tile, void *stream) {
   if (!A || !B || !C || M < 1 || N < 1 || K < 1) return IL_E_ARG;
   if (dtype != IL_F32 && dtype != IL_BF16) return IL_E_ARG;
-  if (epi < EPI_STORE || epi > EPI_WGRAD || tile < 0 || tile > 8) return IL_E_ARG;
+  if (epi < EPI_STORE || epi > EPI_STORE_F16 || tile < 0 || tile > 8) return IL_E_ARG;
+  if (epi == EPI_STORE_F16 && dtype != IL_BF16) return IL_E_ARG;
   if ((epi == EPI_BIAS || epi == EPI_BIAS_GELU || epi == EPI_BIAS_RES) && !bias) return IL_E_ARG;
   if ((epi == EPI_BIAS_RES && !res) || (epi == EPI_BIAS_GELU && !C2)) return IL_E_ARG;
   if (epi == EPI_GELU_BWD && (!aux || aux_wrap < 1)) return IL_E_ARG;

@@ -57,9 +57,13 @@ __global__ __launch_bounds__(256) void xent_rows_kernel(T *z, const int32_t *__r
 // over the NT threads of the workgroup), so the logits tile is read once and written once.
 // The exponentials go straight to the hardware instruction: every argument is <= 0 up to
 // rounding, and a result below 2^-126 may flush to zero.
-template <int J, int NT>
+// F16IN: the logits are IEEE half (the logits GEMM's fp32 accumulators rounded to 11 significant bits instead
+// of bfloat16's 8: the softmax takes exp of them, so their absolute error is the relative error of every
+// probability); the dlogits written back over them are bf16, the operand type of the GEMMs that follow.
+template <int J, int NT, bool F16IN>
 __global__ __launch_bounds__(NT) void xent_rows_reg_kernel(bf16_t *z, const int32_t *__restrict__ targets, int V,
                                                             float inv_n, float *__restrict__ rowloss) {
+  auto cvt = [](uint32_t h) { return F16IN ? f16_to_f32((uint16_t)h) : bf16_to_f32((bf16_t)h); };
   constexpr int NW = NT / 64;
   __shared__ float red[NW];
   const int row = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -71,7 +75,7 @@ __global__ __launch_bounds__(NT) void xent_rows_reg_kernel(bf16_t *z, const int3
     for (int v = tid; v < nvec; v += NT) *reinterpret_cast<uint4 *>(zr + v * 8) = uint4{0u, 0u, 0u, 0u};
     return;
   }
-  const float ztgt = bf16_to_f32(zr[tgt]);  // read before any thread overwrites the row (barriers below)
+  const float ztgt = cvt(zr[tgt]);  // read before any thread overwrites the row (barriers below)
   uint4 q[J];
   float mx = -INFINITY;
 #pragma unroll
@@ -82,8 +86,8 @@ __global__ __launch_bounds__(NT) void xent_rows_reg_kernel(bf16_t *z, const int3
       const uint32_t u[4] = {q[j].x, q[j].y, q[j].z, q[j].w};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        mx = fmaxf(mx, bf16_to_f32((bf16_t)(u[e] & 0xFFFF)));
-        mx = fmaxf(mx, bf16_to_f32((bf16_t)(u[e] >> 16)));
+        mx = fmaxf(mx, cvt(u[e] & 0xFFFF));
+        mx = fmaxf(mx, cvt(u[e] >> 16));
       }
     }
   }
@@ -103,8 +107,8 @@ __global__ __launch_bounds__(NT) void xent_rows_reg_kernel(bf16_t *z, const int3
       const uint32_t u[4] = {q[j].x, q[j].y, q[j].z, q[j].w};
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        se += __builtin_amdgcn_exp2f(bf16_to_f32((bf16_t)(u[e] & 0xFFFF)) * 1.4426950408889634f - mx2);
-        se += __builtin_amdgcn_exp2f(bf16_to_f32((bf16_t)(u[e] >> 16)) * 1.4426950408889634f - mx2);
+        se += __builtin_amdgcn_exp2f(cvt(u[e] & 0xFFFF) * 1.4426950408889634f - mx2);
+        se += __builtin_amdgcn_exp2f(cvt(u[e] >> 16) * 1.4426950408889634f - mx2);
       }
     }
   }
@@ -125,8 +129,8 @@ __global__ __launch_bounds__(NT) void xent_rows_reg_kernel(bf16_t *z, const int3
       float p[8];
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        p[2 * e] = __builtin_amdgcn_exp2f(bf16_to_f32((bf16_t)(u[e] & 0xFFFF)) * 1.4426950408889634f - lse2);
-        p[2 * e + 1] = __builtin_amdgcn_exp2f(bf16_to_f32((bf16_t)(u[e] >> 16)) * 1.4426950408889634f - lse2);
+        p[2 * e] = __builtin_amdgcn_exp2f(cvt(u[e] & 0xFFFF) * 1.4426950408889634f - lse2);
+        p[2 * e + 1] = __builtin_amdgcn_exp2f(cvt(u[e] >> 16) * 1.4426950408889634f - lse2);
       }
       const int c0 = v * 8;
       if (tgt >= c0 && tgt < c0 + 8) {
@@ -147,18 +151,28 @@ __global__ __launch_bounds__(NT) void xent_rows_reg_kernel(bf16_t *z, const int3
 }  // namespace
 
 hipError_t xent_rows(int dtype, void *z, const int32_t *targets, int rows, int V, float inv_n, float *rowloss,
-                     hipStream_t s) {
+                     hipStream_t s, int z_is_f16) {
   if (rows <= 0) return hipSuccess;
+  const bool reg = (V & 7) == 0 && V <= 1024 * 8 * 8;
+  if (z_is_f16 && (dtype == 0 || !reg)) return hipErrorInvalidValue;  // half logits: only the in-register kernels
   if (dtype == 0)
     hipLaunchKernelGGL(xent_rows_kernel<float>, dim3(rows), dim3(256), 0, s, (float *)z, targets, V, inv_n,
                        rowloss);
-  else if ((V & 7) == 0 && V <= 512 * 8 * 8)
-    hipLaunchKernelGGL((xent_rows_reg_kernel<8, 512>), dim3(rows), dim3(512), 0, s, (bf16_t *)z, targets, V, inv_n,
-                       rowloss);
-  else if ((V & 7) == 0 && V <= 1024 * 8 * 8)  // wider rows: twice the threads rather than twice the registers
-    hipLaunchKernelGGL((xent_rows_reg_kernel<8, 1024>), dim3(rows), dim3(1024), 0, s, (bf16_t *)z, targets, V, inv_n,
-                       rowloss);
-  else
+  else if (reg && V <= 512 * 8 * 8) {
+    if (z_is_f16)
+      hipLaunchKernelGGL((xent_rows_reg_kernel<8, 512, true>), dim3(rows), dim3(512), 0, s, (bf16_t *)z, targets, V,
+                         inv_n, rowloss);
+    else
+      hipLaunchKernelGGL((xent_rows_reg_kernel<8, 512, false>), dim3(rows), dim3(512), 0, s, (bf16_t *)z, targets, V,
+                         inv_n, rowloss);
+  } else if (reg) {  // wider rows: twice the threads rather than twice the registers
+    if (z_is_f16)
+      hipLaunchKernelGGL((xent_rows_reg_kernel<8, 1024, true>), dim3(rows), dim3(1024), 0, s, (bf16_t *)z, targets, V,
+                         inv_n, rowloss);
+    else
+      hipLaunchKernelGGL((xent_rows_reg_kernel<8, 1024, false>), dim3(rows), dim3(1024), 0, s, (bf16_t *)z, targets, V,
+                         inv_n, rowloss);
+  } else
     hipLaunchKernelGGL(xent_rows_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, (bf16_t *)z, targets, V, inv_n,
                        rowloss);
   return hipGetLastError();
