@@ -97,6 +97,25 @@ def test_misuse_returns_status_codes():
     assert "IL_E_STATE" in binding.il_status_string(binding.IL_E_STATE)
 
 
+def test_operands_beyond_the_descriptor_range_are_rejected_up_front():
+    """Every GEMM operand is addressed through a 32-bit buffer descriptor: il_init refuses a problem whose
+    largest stacked operand, head matrix or logits tile reaches 2 GiB instead of failing in mid-step."""
+    lib = binding.load()
+    ctx = C.c_void_p()
+    ok = synth.Workload("fits", "bf16", K=2, L=1, d=1024, H=16, m=4096, V=32768, B=64, T=2048, n=2)
+    for w, want in [(ok.with_(B=128), binding.IL_E_SHAPE),                         # 262144 x 4096 x 2 B = 2 GiB
+                    (ok, binding.IL_E_WORKSPACE),                                  # half of it: a size query succeeds
+                    (ok.with_(B=1, T=64, V=1 << 21, d=512, H=8), binding.IL_E_SHAPE),    # head matrix d x V x 2 B = 2 GiB
+                    (ok.with_(B=16, V=1 << 19, n=1), binding.IL_E_SHAPE)]:               # default logits tile 2048 x 2^19 x 2 B
+        cfg = binding.make_config(w)
+        assert lib.il_init(C.byref(cfg), C.byref(ctx)) == want, w
+    cfg = binding.make_config(ok.with_(B=16, V=1 << 19, n=1), head_chunk=512)           # a smaller tile fits
+    assert lib.il_init(C.byref(cfg), C.byref(ctx)) == binding.IL_E_WORKSPACE
+    cfg = binding.make_config(synth.WORKLOADS["tiny"])
+    cfg.profile = 3
+    assert lib.il_init(C.byref(cfg), C.byref(ctx)) == binding.IL_E_ARG
+
+
 def test_pack_unpack_roundtrip():
     import numpy as np
     w = synth.WORKLOADS["tiny"]
