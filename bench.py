@@ -344,6 +344,50 @@ def embedding_line(w, reps=10):
             "peak": PEAK_HBM_GBS, "unit": "GB/s"}
 
 
+def gemm_reference(w, iters=10, rot=6):
+    """Context for the GEMM rates: the library's kernel (il_test_gemm, epilogue = plain store) and the vendor
+    library (torch.matmul, which dispatches to hipBLASLt / rocBLAS) on the headline workload's main GEMM
+    shapes, both timed the same way - HIP events around `iters` launches that rotate through `rot` operand sets,
+    so operands come from HBM / Infinity Cache as they do inside a step.  The vendor library is not part of the
+    product path; this is a yardstick for what a tuned kernel reaches on this board."""
+    import torch
+    from paper_2010_04116_amd import binding as b
+    dev = torch.device("cuda:0")
+    st = torch.cuda.current_stream()
+    N, d, m, V = w.N, w.d, w.m, w.V
+    live = max(b.il_routing_plan(w.K, w.n)[0])
+    nc = min(N // 2, 2048)
+    shapes = [("fwd_qkv", N, 3 * d, d, 0, 1, 0), ("fwd_o", N, d, d, 0, 1, 0), ("fwd_fc1", N, m, d, 0, 1, 0),
+              ("fwd_fc2", N, d, m, 0, 1, 0), (f"dgrad_fc2_{live}streams", live * N, m, d, 0, 0, 0),
+              (f"dgrad_fc1_{live}streams", live * N, d, m, 0, 0, 0), ("wgrad_fc1", d, m, N, 1, 1, 6),
+              ("head_logits", nc, V, d, 0, 1, 0), ("head_dx", nc, d, V, 0, 0, 5)]
+    out = {}
+    def timed(fn):
+        for i in range(3):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for i in range(iters):
+            fn(i)
+        e1.record(st)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+    for name, M, Nn, K, akm, bkm, epi in shapes:
+        As = [(torch.randn((K, M) if akm else (M, K), device=dev) * 0.5).to(torch.bfloat16) for _ in range(rot)]
+        Bs = [(torch.randn((K, Nn) if bkm else (Nn, K), device=dev) * 0.5).to(torch.bfloat16) for _ in range(rot)]
+        C = torch.zeros((M, Nn), device=dev, dtype=torch.float32 if epi in (5, 6) else torch.bfloat16)
+        ours = timed(lambda i: b.il_test_gemm(b.IL_BF16, As[i % rot], Bs[i % rot], M, Nn, K, M if akm else K,
+                                              Nn if bkm else K, akm, bkm, epi, C, stream=st.cuda_stream))
+        lib = timed(lambda i: torch.matmul(As[i % rot].t() if akm else As[i % rot],
+                                           Bs[i % rot] if bkm else Bs[i % rot].t()))
+        fl = 2.0 * M * Nn * K
+        out[name] = {"M": M, "N": Nn, "K": K, "this_library_tflops": fl / ours / 1e9,
+                     "vendor_library_tflops": fl / lib / 1e9}
+        del As, Bs, C
+    return out
+
+
 def measured_peaks(copy_mib=1024):
     """What the board itself reaches: a matrix-unit-only loop and a streaming copy (the library's
     micro-benchmarks), reported beside the nominal peaks the roofline fractions use."""
@@ -421,6 +465,8 @@ def main():
     out.update(res)
     if peaks:
         out["measured_peaks"] = peaks
+    if w.dtype == "bf16" and not a.no_peaks:
+        out["gemm_reference"] = gemm_reference(w)
     out["target"] = {"mfma_utilisation_pct": 50.0, "met": out["mfma_utilisation_pct_of_bf16_peak"] >= 50.0,
                      "note": "north star: >= 50 % of bf16 MFMA peak on the GEMM-dominated configurations"}
     if not a.no_cpu_baseline:
