@@ -38,8 +38,11 @@ int il_profile_read(il_ctx *ctx, int32_t cap, const char **names, int64_t *launc
  * a_kmajor / b_kmajor: 0 = operand stored [rows, K] row-major, 1 = stored [K, rows] row-major;
  * epi: 0 store (T) | 1 +bias (T) | 2 +bias, C = pre-activation, C2 = GELU (T, T) |
  *      3 +bias +res (fp32 out) | 4 * GELU'(aux[row % aux_wrap]) (T) | 5 store fp32 |
- *      6 C = scale*acc (+ C if beta) (fp32) | 7 store as IEEE half, clamped to the finite range (bf16 operands,
- *      forward layout only);
+ *      6 C = scale*acc (+ C if beta) (fp32) | 7 the head's logits tile (bf16 operands, forward layout only, not
+ *      the 64x64 tiles): C = acc as IEEE half, clamped to the finite range; if C2 is given also the softmax
+ *      statistics of the fp32 accumulators: C2 = fp32 [M][G][2], G = ceil(N / 64), (max, sum of exp(z - max)) of
+ *      every group of 64 columns, followed by fp32 [M] target logits z[row, aux[row]] with aux = int32 [M]
+ *      targets (rows whose target is outside [0, N) are left unwritten);
  * tile: 0 = library's choice, else (bf16 only; "+4" = four wavefronts that only load)
  *       1 = 256x256 / 8+4 wavefronts, 2 = 128x128 / 4+4, two K steps staged, 3 = 128x128 / 4+4, four staged,
  *       4 = 64x64 / 4 wavefronts, 5 = 64x64 / 4+4, four staged, 6 = 256x128 / 8+4, three staged,

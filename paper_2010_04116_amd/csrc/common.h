@@ -90,9 +90,12 @@ enum Epi {
   EPI_GELU_BWD = 4,   // C = acc * gelu'(aux[row mod wrap, col])  (T out, T aux)
   EPI_STORE_F32 = 5,  // Cf = acc                                 (fp32 out)
   EPI_WGRAD = 6,      // Cf = scale*acc (+ Cf if beta)            (fp32 out)
-  EPI_STORE_F16 = 7   // C = acc as IEEE half, clamped to +-65504 (bf16 operands only): the head's logits tile,
-                      // whose softmax wants the three extra mantissa bits and never the range
+  EPI_LOGITS = 7      // the head's logits tile (bf16 operands only): C = acc as IEEE half, clamped to +-65504 (the
+                      // softmax wants the three extra mantissa bits and never the range); and, when row_stats is
+                      // set, softmax statistics straight from the fp32 accumulators: for every row and every
+                      // group of 64 columns (max, sum of exp(z - max)), and the row's target logit
 };
+constexpr int kStatGroup = 64;  // columns per statistics group of EPI_LOGITS
 
 struct GemmArgs {
   // C[M,N] = sum_k A(m,k) B(k,n); operand storage:
@@ -117,6 +120,11 @@ struct GemmArgs {
   int tile;           // bf16: 0 = choose by shape, 1 = 256x256, 2 / 3 = 128x128 with 2 / 4 stages, 4 / 5 = 64x64 with 2 / 4,
                       // 6 = 256x128, 7 = 128x256 (three stages), 8 = 256x256 persistent
   int beta;           // EPI_WGRAD: accumulate into C
+  // EPI_LOGITS, all optional together: row_stats [M][ceil(N / kStatGroup)][2] fp32, row_targets [M] int32,
+  // row_ztgt [M] fp32 (written for rows whose target lies in [0, N))
+  float *row_stats;
+  const int32_t *row_targets;
+  float *row_ztgt;
 };
 
 // Events attached to ONE kernel dispatch (hipExtLaunchKernelGGL): elapsed(start, stop) is that
@@ -192,9 +200,14 @@ hipError_t attention_backward(int dtype, const void *qkv, const void *o, const v
 // ---- cross-entropy rows (xent.hip) --------------------------------------------------------
 // For each of `rows` logit rows z (T, [rows, V], in place): rowloss = lse - z[target];
 // z <- (softmax(z) - onehot(target)) * inv_n.
-// bf16 mode: with z_is_f16 the logits arrive as IEEE half (EPI_STORE_F16); dlogits leave as bf16 either way.
 hipError_t xent_rows(int dtype, void *z, const int32_t *targets, int rows, int V, float inv_n,
-                     float *rowloss, hipStream_t s, int z_is_f16 = 0);
+                     float *rowloss, hipStream_t s);
+// The same for a tile of IEEE-half logits whose row statistics the logits GEMM left behind (EPI_LOGITS):
+// stats [rows][ceil(V / kStatGroup)][2] = (max, sum-exp) per 64-column group, ztgt [rows] = target logit.
+// One pass over the tile: the groups are merged into the row's log-sum-exp, rowloss = lse - ztgt, and
+// z (half) <- bf16((exp(z - lse) - onehot) * inv_n).  Any V that is a multiple of 8.
+hipError_t xent_rows_from_stats(void *z, const float *stats, const float *ztgt, const int32_t *targets, int rows,
+                                int V, float inv_n, float *rowloss, hipStream_t s);
 // loss_out[0] = scale * sum(rowloss[0..rows))
 hipError_t sum_scalar(const float *rowloss, int rows, float scale, float *loss_out, hipStream_t s);
 

@@ -49,6 +49,13 @@ __device__ inline u32x4 pack8(const float (&f)[8]) {
   return v;
 }
 
+// A value from another lane of the same 16-lane row through the data-parallel path of the vector ALU (no
+// LDS traffic): CTRL 0xB1 = lane ^ 1, 0x4E = lane ^ 2 (quad permutes), 0x141 = lane 7 - i of each half row.
+template <int CTRL>
+__device__ inline float dpp_f32(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+
 // One row's eight consecutive output columns: the epilogue operation and the store.
 template <int EPI>
 __device__ inline void emit8(const GemmArgs &g, float4 v0, float4 v1, int grow, int gcol, const float (&bv)[8]) {
@@ -57,7 +64,7 @@ __device__ inline void emit8(const GemmArgs &g, float4 v0, float4 v1, int grow, 
   const size_t o = (size_t)grow * g.ldc + gcol;
   if constexpr (EPI == EPI_STORE) {
     *reinterpret_cast<u32x4 *>((bf16_t *)g.C + o) = pack8(v);
-  } else if constexpr (EPI == EPI_STORE_F16) {
+  } else if constexpr (EPI == EPI_LOGITS) {
     u32x4 h;
 #pragma unroll
     for (int i = 0; i < 4; ++i) h[i] = pack_f16x2(v[2 * i], v[2 * i + 1]);
@@ -143,7 +150,46 @@ __device__ inline void epilogue_strips(const GemmArgs &g, floatx16 (&acc)[MI][NI
       const float4 v0 = *reinterpret_cast<const float4 *>(stg + row_in * SP + col_l);
       const float4 v1 = *reinterpret_cast<const float4 *>(stg + row_in * SP + col_l + 4);
       asm volatile("" ::: "memory");
-      emit8<EPI>(g, v0, v1, row0 + i * 32 + p * E::RPP + row_in, gcol, bv);
+      const int grow = row0 + i * 32 + p * E::RPP + row_in;
+      if constexpr (EPI == EPI_LOGITS) {
+        // Softmax statistics of this row's 64 columns from the fp32 accumulators (before any rounding):
+        // the row's eight lanes (consecutive lane ids) each hold eight columns; N is a multiple of 8, so a
+        // lane's columns are all inside the matrix or all outside.
+        static_assert((WTN == kStatGroup && E::LPR == 8) || EPI != EPI_LOGITS, "one statistics group per wave-tile row");
+        if (g.row_stats) {
+          const float v[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+          const bool in = gcol < g.N;
+          float m = -INFINITY;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) m = fmaxf(m, in ? v[e] : -INFINITY);
+          m = fmaxf(m, dpp_f32<0xB1>(m));   // lane ^ 1
+          m = fmaxf(m, dpp_f32<0x4E>(m));   // lane ^ 2
+          m = fmaxf(m, dpp_f32<0x141>(m));  // the other quad of the eight lanes
+          float se = 0.f;
+          if (in) {
+            const float m2 = m * 1.4426950408889634f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) se += __builtin_amdgcn_exp2f(v[e] * 1.4426950408889634f - m2);
+          }
+          se += dpp_f32<0xB1>(se);
+          se += dpp_f32<0x4E>(se);
+          se += dpp_f32<0x141>(se);
+          if (grow < g.M) {
+            if (lane % E::LPR == 0 && col0 < g.N) {
+              float *st = g.row_stats + ((size_t)grow * ((g.N + kStatGroup - 1) / kStatGroup) + col0 / kStatGroup) * 2;
+              st[0] = m;
+              st[1] = se;
+            }
+            const int tgt = g.row_targets[grow];
+            if (in && tgt >= gcol && tgt < gcol + 8) {
+#pragma unroll
+              for (int e = 0; e < 8; ++e)
+                if (gcol + e == tgt) g.row_ztgt[grow] = v[e];
+            }
+          }
+        }
+      }
+      emit8<EPI>(g, v0, v1, grow, gcol, bv);
     }
 }
 
@@ -612,12 +658,16 @@ hipError_t pick_tile(GemmBatch &b, hipStream_t s) {
     t256 += (long)((b.p[i].M + 255) / 256) * ((b.p[i].N + 255) / 256);
     t128 += (long)((b.p[i].M + 127) / 128) * ((b.p[i].N + 127) / 128);
   }
+  if constexpr (EPI == EPI_LOGITS) {
+    // a statistics group is the 64 columns of one wave tile: every tile but the 64x64 ones (32-wide wave tiles)
+    if (b.p[0].tile == 4 || b.p[0].tile == 5) return hipErrorInvalidValue;
+  }
   switch (b.p[0].tile) {
     case 1: return launch_dma<256, 256, 2, 4, 64, 2, AKM, BKM, EPI, 2>(b, s);
     case 2: return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI, 2>(b, s);
     case 3: return launch_dma<128, 128, 2, 2, 64, 4, AKM, BKM, EPI, 2>(b, s);
-    case 4: return launch_dma<64, 64, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
-    case 5: return launch_dma<64, 64, 2, 2, 64, 4, AKM, BKM, EPI, 2>(b, s);
+    case 4: if constexpr (EPI != EPI_LOGITS) return launch_dma<64, 64, 2, 2, 64, 2, AKM, BKM, EPI>(b, s); else break;
+    case 5: if constexpr (EPI != EPI_LOGITS) return launch_dma<64, 64, 2, 2, 64, 4, AKM, BKM, EPI, 2>(b, s); else break;
     case 6: return launch_dma<256, 128, 4, 2, 64, 3, AKM, BKM, EPI, 2>(b, s);
     case 7: return launch_dma<128, 256, 2, 4, 64, 3, AKM, BKM, EPI, 2>(b, s);
     case 8: return launch_persist<256, 256, 2, 4, 64, AKM, BKM, EPI>(b, s);
@@ -639,8 +689,12 @@ hipError_t pick_tile(GemmBatch &b, hipStream_t s) {
     return t128x256 <= t256x128 ? launch_dma<128, 256, 2, 4, 64, 3, AKM, BKM, EPI, 2>(b, s)
                                 : launch_dma<256, 128, 4, 2, 64, 3, AKM, BKM, EPI, 2>(b, s);
   if (t128 > 256) return launch_dma<128, 128, 2, 2, 64, 2, AKM, BKM, EPI, 2>(b, s);
-  if (t64 <= 512) return launch_dma<64, 64, 2, 2, 64, 4, AKM, BKM, EPI, 2>(b, s);
-  return launch_dma<64, 64, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
+  if constexpr (EPI == EPI_LOGITS) {
+    return launch_dma<128, 128, 2, 2, 64, 4, AKM, BKM, EPI, 2>(b, s);  // (never the 32-wide wave tiles)
+  } else {
+    if (t64 <= 512) return launch_dma<64, 64, 2, 2, 64, 4, AKM, BKM, EPI, 2>(b, s);
+    return launch_dma<64, 64, 2, 2, 64, 2, AKM, BKM, EPI>(b, s);
+  }
 }
 
 // argument checks and buffer extents of one problem
@@ -655,6 +709,7 @@ hipError_t prepare(GemmArgs &g) {
   if (g.k_end < 0 || g.k_begin < 0 || g.k_end > g.K || (g.k_end > 0 && g.k_begin >= g.k_end) || (g.k_begin & 7) ||
       (g.k_end & 7))
     return hipErrorInvalidValue;
+  if (g.epi == EPI_LOGITS && g.row_stats && (!g.row_targets || !g.row_ztgt)) return hipErrorInvalidValue;
   const size_t arows = g.a_kmajor ? (size_t)g.K : (size_t)g.M;
   const size_t brows = g.b_kmajor ? (size_t)g.K : (size_t)g.N;
   const size_t ab = arows * g.lda * 2, bb = brows * g.ldb * 2;  // bytes, below 2 GiB
@@ -714,7 +769,7 @@ hipError_t gemm_bf16_batch(const GemmArgs *list, int count, hipStream_t s) {
     case 1:  // activations x weights[K,N]: forward linears, head logits
       switch (g.epi) {
         case EPI_STORE: return pick_tile<false, true, EPI_STORE>(b, s);
-        case EPI_STORE_F16: return pick_tile<false, true, EPI_STORE_F16>(b, s);
+        case EPI_LOGITS: return pick_tile<false, true, EPI_LOGITS>(b, s);
         case EPI_BIAS: return pick_tile<false, true, EPI_BIAS>(b, s);
         case EPI_BIAS_GELU: return pick_tile<false, true, EPI_BIAS_GELU>(b, s);
         case EPI_BIAS_RES: return pick_tile<false, true, EPI_BIAS_RES>(b, s);

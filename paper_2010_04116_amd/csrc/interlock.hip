@@ -198,7 +198,7 @@ struct il_ctx {
   int flush_idx = 0;
   SumColsumJobs pending; float *pending_out[kMaxSumColsumJobs]; int pending_acc[kMaxSumColsumJobs];
   double pending_bytes = 0;
-  char *xb, *Z; float *rowloss, *dxh;
+  char *xb, *Z; float *rowloss, *dxh, *hstats = nullptr, *hztgt = nullptr;
   int Nc;
   std::vector<char> fwd_done, head_done, bwd_done;
   // heads run on a side stream, concurrently with the next component's forward
@@ -244,6 +244,11 @@ size_t layout_params(il_ctx *c) {
     c->hoff[k] = o; o += d * (size_t)c->V;
   }
   return o;
+}
+
+// bf16: (max, sum-exp) per row of the logits tile and per group of kStatGroup vocabulary columns
+size_t head_stats_bytes(const il_ctx *c) {
+  return c->eb == 2 ? (size_t)c->Nc * ((c->V + kStatGroup - 1) / kStatGroup) * 2 * 4 : 0;
 }
 
 size_t layout_workspace(il_ctx *c, void *base) {
@@ -293,6 +298,8 @@ size_t layout_workspace(il_ctx *c, void *base) {
   c->xb = (char *)cv.take(N * d * eb);
   c->Z = (char *)cv.take((size_t)c->Nc * c->V * eb);
   c->rowloss = (float *)cv.take(N * 4);
+  c->hstats = (float *)cv.take(head_stats_bytes(c));
+  c->hztgt = (float *)cv.take(eb == 2 ? (size_t)c->Nc * 4 : 0);
   c->dxh = (float *)cv.take((size_t)c->K * N * d * 4);
   return cv.off;
 }
@@ -791,6 +798,7 @@ int il_stage_forward(il_ctx *c, int32_t k, const float *x_in, float *x_out) {
 // il_head_xent_static from the library's static device array.
 struct HeadScratch {
   char *xb, *Z; float *rowloss, *skws; size_t skws_floats;
+  float *stats, *ztgt;  // bf16: per-row softmax statistics of the tile ([Nc][ceil(V/64)][2]) and target logits ([Nc])
 };
 
 static int head_xent_impl(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets, float *loss_out,
@@ -838,16 +846,22 @@ static int head_xent_impl(il_ctx *c, int32_t k, const float *x_k, const int32_t 
     g.A = xc; g.lda = d; g.a_kmajor = 0;
     g.B = P(c, c->hoff[k - 1]); g.ldb = V; g.b_kmajor = 1;
     // bf16 mode: the tile holds the logits as IEEE half (three more mantissa bits for the softmax's
-    // exponentials) whenever the in-register cross-entropy kernel can take the row
-    const bool zf16 = dt == IL_BF16 && V <= 65536;
-    g.M = rows; g.N = V; g.K = d; g.epi = zf16 ? EPI_STORE_F16 : EPI_STORE; g.C = hs.Z; g.ldc = V;
+    // exponentials) and the GEMM's epilogue leaves the softmax statistics of every 64-column group,
+    // taken from its fp32 accumulators, and the target logits beside it
+    const bool fused = dt == IL_BF16;
+    g.M = rows; g.N = V; g.K = d; g.epi = fused ? EPI_LOGITS : EPI_STORE; g.C = hs.Z; g.ldc = V;
+    if (fused) { g.row_stats = hs.stats; g.row_targets = targets + r0; g.row_ztgt = hs.ztgt; }
     {
       Scope sc(c, KC_GEMM_HEAD, 2.0 * rows * V * d, gemm_bytes(c, g));
       IL_TRY(gemm(c, g));
     }
     {
       Scope sc(c, KC_XENT, 0, 2.0 * rows * V * eb);
-      IL_TRY(xent_rows(dt, hs.Z, targets + r0, rows, V, c->grad_scale / N, hs.rowloss + r0, c->stream, zf16));
+      if (fused)
+        IL_TRY(xent_rows_from_stats(hs.Z, hs.stats, hs.ztgt, targets + r0, rows, V, c->grad_scale / N,
+                                    hs.rowloss + r0, c->stream));
+      else
+        IL_TRY(xent_rows(dt, hs.Z, targets + r0, rows, V, c->grad_scale / N, hs.rowloss + r0, c->stream));
     }
     g = base_args();  // dx = dz W_h^T
     g.A = hs.Z; g.lda = V; g.a_kmajor = 0;
@@ -915,7 +929,7 @@ static int head_xent_impl(il_ctx *c, int32_t k, const float *x_k, const int32_t 
 
 int il_head_xent(il_ctx *c, int32_t k, const float *x_k, const int32_t *targets, float *loss_out) {
   if (!c) return IL_E_ARG;
-  const HeadScratch hs{c->xb, c->Z, c->rowloss, c->skws, c->skws_floats};
+  const HeadScratch hs{c->xb, c->Z, c->rowloss, c->skws, c->skws_floats, c->hstats, c->hztgt};
   return head_xent_impl(c, k, x_k, targets, loss_out, hs, false);
 }
 
@@ -955,10 +969,13 @@ int il_head_xent_static(il_ctx *c, int32_t k, const float *x_k, const int32_t *t
   const size_t o_z = cv.off; cv.take((size_t)c->Nc * c->V * c->eb);
   const size_t o_rl = cv.off; cv.take((size_t)c->N * 4);
   const size_t o_sk = cv.off; cv.take(c->skws_floats * 4);
+  const size_t o_hs = cv.off; cv.take(head_stats_bytes(c));
+  const size_t o_zt = cv.off; cv.take(c->eb == 2 ? (size_t)c->Nc * 4 : 0);
   if (cv.off > kStaticScratchBytes) return IL_E_WORKSPACE;
   char *base = nullptr;
   { const int rc = static_scratch(&base); if (rc) return rc; }
-  const HeadScratch hs{base + o_xb, base + o_z, (float *)(base + o_rl), (float *)(base + o_sk), c->skws_floats};
+  const HeadScratch hs{base + o_xb, base + o_z, (float *)(base + o_rl), (float *)(base + o_sk), c->skws_floats,
+                       (float *)(base + o_hs), (float *)(base + o_zt)};
   return head_xent_impl(c, k, x_k, targets, loss_out, hs, true);
 }
 
@@ -1047,8 +1064,8 @@ int il_test_gemm(int32_t dtype, const void *A, const void *B, int32_t M, int32_t
                  int32_t beta, int32_t tile, void *stream) {
   if (!A || !B || !C || M < 1 || N < 1 || K < 1) return IL_E_ARG;
   if (dtype != IL_F32 && dtype != IL_BF16) return IL_E_ARG;
-  if (epi < EPI_STORE || epi > EPI_STORE_F16 || tile < 0 || tile > 8) return IL_E_ARG;
-  if (epi == EPI_STORE_F16 && dtype != IL_BF16) return IL_E_ARG;
+  if (epi < EPI_STORE || epi > EPI_LOGITS || tile < 0 || tile > 8) return IL_E_ARG;
+  if (epi == EPI_LOGITS && (dtype != IL_BF16 || (C2 && !aux))) return IL_E_ARG;
   if ((epi == EPI_BIAS || epi == EPI_BIAS_GELU || epi == EPI_BIAS_RES) && !bias) return IL_E_ARG;
   if ((epi == EPI_BIAS_RES && !res) || (epi == EPI_BIAS_GELU && !C2)) return IL_E_ARG;
   if (epi == EPI_GELU_BWD && (!aux || aux_wrap < 1)) return IL_E_ARG;
@@ -1056,6 +1073,13 @@ int il_test_gemm(int32_t dtype, const void *A, const void *B, int32_t M, int32_t
   g.A = A; g.B = B; g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb;
   g.a_kmajor = a_kmajor != 0; g.b_kmajor = b_kmajor != 0; g.epi = epi; g.C = C; g.C2 = C2; g.ldc = ldc;
   g.bias = bias; g.res = res; g.aux = aux; g.aux_wrap = aux_wrap; g.scale = scale; g.beta = beta; g.tile = tile;
+  if (epi == EPI_LOGITS && C2) {  // statistics and target logits share the second output buffer
+    g.row_stats = (float *)C2;
+    g.row_targets = (const int32_t *)aux;
+    g.row_ztgt = (float *)C2 + (size_t)M * ((N + kStatGroup - 1) / kStatGroup) * 2;
+    g.C2 = nullptr;
+    g.aux = nullptr;
+  }
   const hipError_t e = dtype == IL_F32 ? gemm_f32(g, (hipStream_t)stream) : gemm_bf16(g, (hipStream_t)stream);
   return e == hipSuccess ? IL_OK : (e == hipErrorInvalidValue ? IL_E_SHAPE : IL_E_HIP);
 }

@@ -134,6 +134,49 @@ def test_persistent_kernel_second_round_ragged(tile):
         run_case(M, N, 128, akm, bkm, epi, tile, seed=70 + i, beta=int(epi == 6))
 
 
+@pytest.mark.parametrize("tile", [0, 1, 2, 3, 6, 7, 8])
+def test_logits_epilogue_statistics(tile):
+    """The head's logits GEMM leaves, beside the half-precision tile, the softmax statistics of every
+    64-column group taken from its fp32 accumulators, and each row's target logit: checked against the
+    float64 product (ragged M and N, a last group of 40 columns, targets at both ends and out of range)."""
+    import torch
+    dev = torch.device("cuda:0")
+    for M, N, K, seed in ((300, 1000, 192, 90), (520, 4104, 128, 91)):
+        rng = np.random.default_rng(seed)
+        A = _bf16(rng.standard_normal((M, K)))
+        B = _bf16(rng.standard_normal((K, N)) * 0.7)
+        acc = A.astype(np.float64) @ B.astype(np.float64)
+        tgt = rng.integers(0, N, size=M).astype(np.int32)
+        tgt[:4] = [0, N - 1, -1, N]                      # edges, and two ignored positions
+        G = (N + 63) // 64
+        dA = torch.from_numpy(A).to(torch.bfloat16).to(dev)
+        dB = torch.from_numpy(B).to(torch.bfloat16).to(dev)
+        C = torch.zeros((M, N), dtype=torch.bfloat16, device=dev)
+        S = torch.full((M * G * 2 + M,), -7.0, dtype=torch.float32, device=dev)
+        b.il_test_gemm(b.IL_BF16, dA, dB, M, N, K, K, N, 0, 1, 7, C, C2=S, aux=torch.from_numpy(tgt).to(dev), tile=tile,
+                       stream=torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        z = C.view(torch.float16).float().cpu().numpy().astype(np.float64)
+        assert np.abs(z - acc).max() <= 2 ** -10 * np.abs(acc).max() + 1e-6
+        s = S.cpu().numpy().astype(np.float64)
+        st, zt = s[:M * G * 2].reshape(M, G, 2), s[M * G * 2:]
+        pad = np.full((M, G * 64), -np.inf)
+        pad[:, :N] = acc
+        grp = pad.reshape(M, G, 64)
+        m = grp.max(axis=2)
+        se = np.exp(grp - m[:, :, None]).sum(axis=2)
+        assert np.abs(st[:, :, 0] - m).max() <= 1e-5 * np.abs(acc).max(), (M, N, tile)
+        assert np.abs(st[:, :, 1] / se - 1).max() <= 2e-5, (M, N, tile)
+        lse = np.log((st[:, :, 1] * np.exp(st[:, :, 0] - st[:, :, 0].max(axis=1, keepdims=True))).sum(axis=1)) \
+            + st[:, :, 0].max(axis=1)
+        ref = np.log(np.exp(acc - acc.max(axis=1, keepdims=True)).sum(axis=1)) + acc.max(axis=1)
+        assert np.abs(lse - ref).max() <= 2e-5, (M, N, tile)
+        ok = (tgt >= 0) & (tgt < N)
+        want = acc[np.arange(M)[ok], tgt[ok]]
+        assert np.abs(zt[ok] - want).max() <= 1e-5 * np.abs(acc).max(), (M, N, tile)
+        assert np.all(zt[~ok] == -7.0)                       # ignored rows are left alone
+
+
 def test_unsupported_combinations_are_rejected():
     import torch
     dev = torch.device("cuda:0")
@@ -143,6 +186,9 @@ def test_unsupported_combinations_are_rejected():
     assert e.value.status == b.IL_E_SHAPE
     with pytest.raises(b.InterlockError):            # N not a multiple of 8
         b.il_test_gemm(b.IL_BF16, x, x, 64, 60, 64, 64, 64, 0, 0, 0, x, ldc=64)
+    with pytest.raises(b.InterlockError) as e:       # the logits epilogue has no 64x64 tile (32-wide wave tiles)
+        b.il_test_gemm(b.IL_BF16, x, x, 64, 64, 64, 64, 64, 0, 1, 7, x, tile=4)
+    assert e.value.status == b.IL_E_SHAPE
 
 
 
