@@ -155,15 +155,16 @@ int il_head_xent(il_ctx *ctx, int32_t k, const float *x_k, const int32_t *target
  * il_head_xent for callers that cannot allocate or hand over scratch memory for the head (code under
  * HIP graph capture, tight serving or evaluation loops, harnesses that forbid hipMalloc): the same
  * computation and results as il_head_xent(ctx, k, ...), but the head's scratch - the copy of x_k in
- * the GEMM element type, the one logits tile, the per-row losses and the split-K partial products of
- * dL_k/dx_k - lives in a static device array of the library (64 MiB = 67108864 bytes, held
+ * the GEMM element type, the one logits tile with its row statistics, the per-row losses and the
+ * split-K partial products of dL_k/dx_k - lives in a static device array of the library (64 MiB = 67108864 bytes, held
  * by every GPU the library runs on until the process ends) instead of the context's workspace, and the
  * head runs in line on il_config.stream (the library's internal stream and its events are neither
  * created nor used).  The call allocates nothing: no hipMalloc / hipFree, no stream or event creation.
  * Inputs and outputs are as for il_head_xent (x_k, targets, loss_out; head gradients into `grads`,
  * dL_k/dx_k into the context's gradient stream).
  * IL_E_WORKSPACE when batch*seq*d_model + head_chunk*vocab elements of `dtype` + batch*seq*4 bytes +
- * the split-K partials (8 * head_chunk * d_model floats) exceed the static array; IL_E_SHAPE when
+ * the split-K partials (8 * head_chunk * d_model floats) + in bf16 the tile's softmax statistics
+ * (head_chunk * (ceil(vocab/64) * 8 + 4) bytes) exceed the static array; IL_E_SHAPE when
  * head_blocks > 0 (such heads keep activations in the workspace; use il_head_xent); IL_E_HIP when the
  * array's address on the current device cannot be resolved.  Nothing in the array has to start at
  * zero: every piece is written before it is read within the call.  All calls on one GPU share the one
