@@ -32,7 +32,7 @@ PEAK_HBM_GBS = 8000.0
 # profiles/traffic_<workload>.md.  bench.py cannot run the profiler on itself, so the figures are
 # carried here for the workloads they were measured on and are null for any other.
 MEASURED_TRAFFIC = {
-    "small_bf16_n2": 41.88e6,   # 32.18 MB read + 9.70 MB written per launch, 768 launches
+    "small_bf16_n2": 41.98e6,   # 32.189 MB read + 9.788 MB written per launch, 1536 launches
     "large_bf16_n2": 479.18e6,  # 390.21 MB read + 88.97 MB written per launch, 4320 launches (2.15 x algorithmic)
     "medium_bf16_n2": 179.41e6,  # 140.99 + 38.42 MB, 2880 launches (1.88 x)
     "many_head_bf16_n3": 230.62e6,  # 181.06 + 49.56 MB, 3168 launches (1.90 x)
