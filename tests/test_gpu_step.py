@@ -318,23 +318,29 @@ def test_profiling_mode_same_results_and_sane_times():
 
 def test_bf16_two_stream_mode_is_bitwise_the_single_stream_mode():
     """The default mode runs heads, stream sums, column sums and weight gradients on a second stream
-    over double-buffered operands; the profiling mode runs everything in line on one stream.  Three
+    over double-buffered operands; profiling mode 1 runs everything in line on one stream, mode 2 is the
+    default mode with timers attached to the GEMM dispatches.  Three
     blocks per component, two live streams, all heads live: EVERY loss, component, head and input
     gradient must come out bit for bit the same in both modes and in a repeated step."""
     w = synth.Workload("bits", "bf16", K=3, L=3, d=256, H=4, m=1024, V=2048, B=2, T=128, n=2)
     params, x0, tgt = make_inputs(w, seed=17)
     flat = binding.pack_params(w, params)
     runs = []
-    for profile in (False, False, True):
+    for profile in (0, 0, 1, 2):
         st = binding.Step(w, flat, profile=profile)
         st.set_inputs(x0, tgt)
         st.run()
-        if not profile:
+        if profile == 0:
             st.run()                              # and a second step on the same context
         runs.append(st.results())
+        if profile == 2:                          # two streams, timers on the GEMM dispatches only
+            prof = binding.il_profile_read(st.ctx)
+            for k, v in prof.items():
+                assert v["ms"] == 0.0
+                assert (v["kernel_ms"] > 0 and v["launches"] > 0) == k.startswith("gemm"), (k, v)
         st.close()
     a = runs[0]
-    for which, b in (("repeat", runs[1]), ("single-stream", runs[2])):
+    for which, b in (("repeat", runs[1]), ("single-stream", runs[2]), ("timed two-stream", runs[3])):
         assert np.array_equal(a["losses"], b["losses"]), which
         assert np.array_equal(a["dx0"], b["dx0"]), which
         for k in range(w.K):
