@@ -452,14 +452,19 @@ int flush_colsums(il_ctx *c) {
 // the bias-gradient column sum.  The GEMM itself is only described here (`out`); the four weight
 // gradients of a block are launched together at the end of the block's backward so that their
 // tiles share one grid.  `keep`: dy is overwritten before then, so the sum must be materialised
-// even for a single stream of weight 1.
+// even for a single stream of weight 1.  `direct`: dy IS the block's double-buffered operand
+// YS[slot] - a single stream of weight 1 whose producer wrote straight into it - so nothing is
+// copied and the reduction only reads.
 int linear_wgrad(il_ctx *c, const Run &cp, const void *x, const void *dy, int Kin, int Nout, size_t w_off,
-                 size_t b_off, int slot, bool keep, GemmArgs *out, int *nout) {
+                 size_t b_off, int slot, bool keep, bool direct, GemmArgs *out, int *nout) {
   if (cp.nweighted == 0) return IL_OK;  // pass-through streams only: nothing is credited
   // (with the block tail on the side stream every operand is materialised: the scratch it would
   // be read from is rewritten by the next block meanwhile)
-  const bool in_place = cp.nweighted == 1 && cp.wscale == 1.f && !keep && (c->cfg.profile == 1 || c->tail_inline);
-  const char *dys = in_place ? (const char *)dy + (size_t)cp.first_weighted * c->N * Nout * c->eb : c->YS[slot];
+  const bool in_place =
+      direct || (cp.nweighted == 1 && cp.wscale == 1.f && !keep && (c->cfg.profile == 1 || c->tail_inline));
+  const char *dys = direct     ? (const char *)dy
+                    : in_place ? (const char *)dy + (size_t)cp.first_weighted * c->N * Nout * c->eb
+                               : c->YS[slot];
   {
     // queued: two of a block's four reductions are ready at the same point of the backward and
     // share one launch (flush_colsums)
@@ -611,20 +616,27 @@ int block_backward(il_ctx *c, const Run &cp, const BlockOff &b, const BlockSave 
     }
     return IL_OK;
   };
+  // A single stream of weight 1 (all of n = 1 and n = K, the ends of the stack otherwise): the two wide
+  // data gradients - into the MLP's hidden layer and into Q|K|V - are produced straight into this
+  // block's half of the double-buffered weight-gradient operands, so the stream-sum pass has nothing
+  // to copy there.  (The two model-width operands are the gradient stream itself, which the
+  // LayerNorm backward rewrites; they are still copied.)
+  const bool direct = async_tail && cp.cnt == 1 && cp.nweighted == 1 && cp.wscale == 1.f;
+  char *DU = direct ? c->YS[1] : c->DU, *DQKV = direct ? c->YS[3] : c->DQKV;
   // MLP
-  if ((rc = linear_dgrad(c, Gb, b.w_fc2, S, m, d, EPI_GELU_BWD, c->DU, s.u, N))) return rc;
-  if ((rc = linear_wgrad(c, cp, s.gl, Gb, m, d, b.w_fc2, b.b_fc2, 0, true, wg, &nw))) return rc;
-  if ((rc = linear_wgrad(c, cp, s.h2, c->DU, d, m, b.w_fc1, b.b_fc1, 1, false, wg, &nw))) return rc;
-  if ((rc = linear_dgrad(c, c->DU, b.w_fc1, S, d, m, EPI_STORE, c->DH, nullptr, 0))) return rc;
+  if ((rc = linear_dgrad(c, Gb, b.w_fc2, S, m, d, EPI_GELU_BWD, DU, s.u, N))) return rc;
+  if ((rc = linear_wgrad(c, cp, s.gl, Gb, m, d, b.w_fc2, b.b_fc2, 0, true, false, wg, &nw))) return rc;
+  if ((rc = linear_wgrad(c, cp, s.h2, DU, d, m, b.w_fc1, b.b_fc1, 1, false, direct, wg, &nw))) return rc;
+  if ((rc = linear_dgrad(c, DU, b.w_fc1, S, d, m, EPI_STORE, c->DH, nullptr, 0))) return rc;
   if ((rc = flush_colsums(c))) return rc;  // the stream is about to change
   if ((rc = wait_flush(1))) return rc;
   if ((rc = ln_bwd(c, cp, c->DH, s.a, s.st2, b.ln2_g, G, Gb2, 4))) return rc;
   // attention
-  if ((rc = linear_wgrad(c, cp, s.o, Gb2, d, d, b.w_o, b.b_o, 2, true, wg, &nw))) return rc;
+  if ((rc = linear_wgrad(c, cp, s.o, Gb2, d, d, b.w_o, b.b_o, 2, true, false, wg, &nw))) return rc;
   if ((rc = linear_dgrad(c, Gb2, b.w_o, S, d, d, EPI_STORE, c->DH, nullptr, 0))) return rc;
-  if ((rc = attention_bwd(c, s, c->DH, cp.cnt, c->DQKV))) return rc;
-  if ((rc = linear_wgrad(c, cp, s.h1, c->DQKV, d, 3 * d, b.w_qkv, b.b_qkv, 3, false, wg, &nw))) return rc;
-  if ((rc = linear_dgrad(c, c->DQKV, b.w_qkv, S, d, 3 * d, EPI_STORE, c->DH, nullptr, 0))) return rc;
+  if ((rc = attention_bwd(c, s, c->DH, cp.cnt, DQKV))) return rc;
+  if ((rc = linear_wgrad(c, cp, s.h1, DQKV, d, 3 * d, b.w_qkv, b.b_qkv, 3, false, direct, wg, &nw))) return rc;
+  if ((rc = linear_dgrad(c, DQKV, b.w_qkv, S, d, 3 * d, EPI_STORE, c->DH, nullptr, 0))) return rc;
   if ((rc = flush_colsums(c))) return rc;
   if ((rc = wait_flush(0))) return rc;
   if ((rc = ln_bwd(c, cp, c->DH, s.xs, s.st1, b.ln1_g, G, Gb, 5))) return rc;

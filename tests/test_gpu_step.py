@@ -316,13 +316,16 @@ def test_profiling_mode_same_results_and_sane_times():
             assert prof[k]["kernel_ms"] == 0.0
 
 
-def test_bf16_two_stream_mode_is_bitwise_the_single_stream_mode():
+@pytest.mark.parametrize("n", [2, 1, 3])
+def test_bf16_two_stream_mode_is_bitwise_the_single_stream_mode(n):
     """The default mode runs heads, stream sums, column sums and weight gradients on a second stream
     over double-buffered operands; profiling mode 1 runs everything in line on one stream, mode 2 is the
     default mode with timers attached to the GEMM dispatches.  Three
     blocks per component, two live streams, all heads live: EVERY loss, component, head and input
     gradient must come out bit for bit the same in both modes and in a repeated step."""
-    w = synth.Workload("bits", "bf16", K=3, L=3, d=256, H=4, m=1024, V=2048, B=2, T=128, n=2)
+    # (n = 1 and n = K: every block carries a single stream of weight 1, whose wide data gradients are
+    # produced straight into the double-buffered weight-gradient operands)
+    w = synth.Workload("bits", "bf16", K=3, L=3, d=256, H=4, m=1024, V=2048, B=2, T=128, n=n)
     params, x0, tgt = make_inputs(w, seed=17)
     flat = binding.pack_params(w, params)
     runs = []
