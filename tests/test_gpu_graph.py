@@ -21,8 +21,10 @@ def _all_equal(w, a, b, what):
                 assert np.array_equal(a["comp_grads"][k][l][name], b["comp_grads"][k][l][name]), (what, k, l, name)
 
 
-@pytest.mark.parametrize("name", ["bits", "small"])
-def test_graph_replays_equal_the_eager_step(name):
+@pytest.mark.parametrize("name,static_heads", [("bits", False), ("small", False), ("bits", True)])
+def test_graph_replays_equal_the_eager_step(name, static_heads):
+    """static_heads: the heads run through il_head_xent_static (scratch in the library's static device
+    array, everything in line on the captured stream) - the entry point meant for callers under capture."""
     import torch
     if name == "small":
         w = synth.WORKLOADS["small"]
@@ -34,15 +36,15 @@ def test_graph_replays_equal_the_eager_step(name):
     st = binding.Step(w, binding.pack_params(w, params), stream=stream)
     with torch.cuda.stream(stream):
         st.set_inputs(x0, tgt)
-        st.run()                                   # eager: also creates the library's stream and events
+        st.run(static_heads)                       # eager: also creates the library's stream and events
         eager = st.results()
         st.set_inputs(x0b, tgtb)
-        st.run()
+        st.run(static_heads)
         eager_b = st.results()
     stream.synchronize()
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g, stream=stream):
-        st.run()
+        st.run(static_heads)
     torch.cuda.synchronize()
     with torch.cuda.stream(stream):
         for rep in range(3):
@@ -52,7 +54,7 @@ def test_graph_replays_equal_the_eager_step(name):
             st.losses.zero_()
             g.replay()
             _all_equal(w, st.results(), want, f"{name} replay {rep}")
-            st.run()                               # and an eager step on the same context afterwards
+            st.run(static_heads)                   # and an eager step on the same context afterwards
             _all_equal(w, st.results(), want, f"{name} eager after replay {rep}")
     del g
     st.close()
