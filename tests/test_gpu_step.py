@@ -470,6 +470,11 @@ def test_large_full_size():
     _full_size("large", 13)
 
 
+def test_large_full_size_global_equivalent():
+    """Large with n = K = 6: every head's stream merges into the one global backward."""
+    _full_size("large", 13, n=6)
+
+
 def test_paper_shape_full_size():
     """The paper's module shape (head width 256, sequences of 128, 6 blocks per module, 2-block heads)."""
     _full_size("paper", 14)
