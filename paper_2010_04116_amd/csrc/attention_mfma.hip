@@ -98,6 +98,32 @@ struct TokTile {
   }
 };
 
+
+// Which causal tile a workgroup takes.  Tiles differ in length (rank 0 = longest, rank nx-1 =
+// shortest, lengths in the ratio nx : nx-1 : ... : 1) while the hardware hands workgroups to the
+// chip's 8 XCDs round-robin by linear id and, inside an XCD, to its 32 CUs round-robin - the
+// natural (x, y) order would give one XCD all the longest tiles and put two of them on each of
+// its CUs.  Here every XCD receives the same mix of lengths, the 32 workgroups that start first
+// on an XCD are its longest and the 32 that join them on the same CUs its shortest, in opposite
+// order, so the two workgroups that share a CU add up to the same work everywhere; later rounds
+// likewise.  Only the assignment of work to workgroups changes, never the result.
+struct CausalTile {
+  int rank, y;
+};
+__device__ inline CausalTile causal_tile() {
+  const int nx = gridDim.x, ny = gridDim.y;
+  const int L = blockIdx.x + nx * blockIdx.y;
+  if ((ny & 7) != 0) return {(int)blockIdx.x, (int)blockIdx.y};
+  const int j = L & 7, s = L >> 3, c = ny >> 3, P = nx * c;  // XCD, slot in the XCD, tiles per length and per XCD
+  const int full = P & ~63, rho = s >> 6, w = s & 63;
+  int i;  // position in the XCD's list of tiles sorted by decreasing length
+  if (s < full)
+    i = w < 32 ? 32 * rho + w : P - 1 - (32 * rho + (w - 32));
+  else
+    i = (full >> 1) + (s - full);
+  return {i / c, j + 8 * (i % c)};
+}
+
 // ------------------------------------------------------------------ forward -------------
 // grid (ceil(T/128), B*H); 4 wavefronts, each owns 32 queries; key tiles of 64.
 template <int DH>
@@ -110,8 +136,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(DH > 128 ? 
   __shared__ __attribute__((aligned(16))) char smem[2 * STAGE];
   const int t = threadIdx.x, lane = t & 63, hh = lane >> 5, lq = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int qt = gridDim.x - 1 - blockIdx.x;  // long rows first
-  const int b = blockIdx.y / H, h = blockIdx.y % H;
+  const CausalTile ct = causal_tile();
+  const int qt = gridDim.x - 1 - ct.rank;  // the last query tile is the longest
+  const int b = ct.y / H, h = ct.y % H;
   const int d = H * DH;
   const size_t ld3 = 3 * (size_t)d;
   const bf16_t *qbase = qkv + (size_t)b * T * ld3 + h * DH;
@@ -269,8 +296,9 @@ __device__ __forceinline__ void attn_bwd_dq_body(const bf16_t *__restrict__ qkv,
   __shared__ __attribute__((aligned(16))) char smem[2 * STAGE];
   const int t = threadIdx.x, lane = t & 63, hh = lane >> 5, lq = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int qt = gridDim.x - 1 - blockIdx.x;
-  const int b = blockIdx.y / H, h = blockIdx.y % H, sidx = blockIdx.z;
+  const CausalTile ct = causal_tile();
+  const int qt = gridDim.x - 1 - ct.rank;
+  const int b = ct.y / H, h = ct.y % H, sidx = blockIdx.z;
   const int d = H * DH;
   const size_t ld3 = 3 * (size_t)d, N = (size_t)B * T;
   const bf16_t *qbase = qkv + (size_t)b * T * ld3 + h * DH;
@@ -301,7 +329,7 @@ __device__ __forceinline__ void attn_bwd_dq_body(const bf16_t *__restrict__ qkv,
     }
   }
   dsv += __shfl_xor(dsv, 32, 64);
-  const size_t sidx_row = (sidx * (size_t)B * H + blockIdx.y) * T;
+  const size_t sidx_row = (sidx * (size_t)B * H + ct.y) * T;
   if (q < T && hh == 0) dsum[sidx_row + q] = dsv;
   const float sc = rsqrtf((float)DH);
   const float sc2 = sc * kLog2e;
@@ -409,15 +437,16 @@ __device__ __forceinline__ void attn_bwd_dkv_body(const bf16_t *__restrict__ qkv
   typedef TokTile<BQ, DH> Tile;
   const int t = threadIdx.x, lane = t & 63, hh = lane >> 5, lk_ = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-  const int b = blockIdx.y / H, h = blockIdx.y % H;
+  const CausalTile ct = causal_tile();  // the first key tile is the longest
+  const int b = ct.y / H, h = ct.y % H;
   const int d = H * DH;
   const size_t ld3 = 3 * (size_t)d, N = (size_t)B * T;
   const bf16_t *qbase = qkv + (size_t)b * T * ld3 + h * DH;
   const bf16_t *kbase = qbase + d, *vbase = qbase + 2 * d;
   const bf16_t *gbase = d_o + (sidx * N + (size_t)b * T) * d + h * DH;
   const float *lrow = lse + ((size_t)b * H + h) * T;
-  const float *drow = dsum + (sidx * (size_t)B * H + blockIdx.y) * T;
-  const int kv0 = blockIdx.x * BKV, kvw0 = kv0 + 32 * wave, kv = kvw0 + lk_;
+  const float *drow = dsum + (sidx * (size_t)B * H + ct.y) * T;
+  const int kv0 = ct.rank * BKV, kvw0 = kv0 + 32 * wave, kv = kvw0 + lk_;
   const int qt0 = kv0 / BQ, nqt = (T + BQ - 1) / BQ;
 
   Frag kf[DH / 16], vf[DO_DK ? DH / 16 : 1];

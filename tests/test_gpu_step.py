@@ -213,6 +213,16 @@ def test_bf16_reduced_small():
     say("worst", summary(compare(w, got, ref, "small_q")))
 
 
+@pytest.mark.parametrize("head_chunk", [64, 192])          # 256 token rows: 4 equal chunks; 192 + a ragged 64
+def test_bf16_head_in_several_chunks(head_chunk):
+    """The head of the bf16 path over several token chunks: statistics, in-place dlogits and dx per chunk,
+    the head matrix's gradient accumulated over the chunks (the default is one chunk of up to 4096 rows)."""
+    w = _small_q()
+    say("case bf16 head_chunk =", head_chunk)
+    got, ref = run_both(w, seed=4, head_chunk=head_chunk)
+    say("worst", summary(compare(w, got, ref, f"small_q head_chunk={head_chunk}")))
+
+
 @pytest.mark.parametrize("T,H", [(96, 4), (160, 2), (32, 4), (224, 2), (128, 1), (96, 1)])
 def test_bf16_sequence_lengths_off_the_attention_tiles(T, H):
     """Sequence lengths that are not multiples of the 64- / 128-row attention tiles, for both MFMA

@@ -106,9 +106,11 @@ def test_operands_beyond_the_descriptor_range_are_rejected_up_front():
     for w, want in [(ok.with_(B=128), binding.IL_E_SHAPE),                         # 262144 x 4096 x 2 B = 2 GiB
                     (ok, binding.IL_E_WORKSPACE),                                  # half of it: a size query succeeds
                     (ok.with_(B=1, T=64, V=1 << 21, d=512, H=8), binding.IL_E_SHAPE),    # head matrix d x V x 2 B = 2 GiB
-                    (ok.with_(B=16, V=1 << 19, n=1), binding.IL_E_SHAPE)]:               # default logits tile 2048 x 2^19 x 2 B
+                    (ok.with_(B=16, V=1 << 19, n=1), binding.IL_E_WORKSPACE)]:           # the default chunk shrinks to fit
         cfg = binding.make_config(w)
         assert lib.il_init(C.byref(cfg), C.byref(ctx)) == want, w
+    cfg = binding.make_config(ok.with_(B=16, V=1 << 19, n=1), head_chunk=2048)          # logits tile 2048 x 2^19 x 2 B
+    assert lib.il_init(C.byref(cfg), C.byref(ctx)) == binding.IL_E_SHAPE
     cfg = binding.make_config(ok.with_(B=16, V=1 << 19, n=1), head_chunk=512)           # a smaller tile fits
     assert lib.il_init(C.byref(cfg), C.byref(ctx)) == binding.IL_E_WORKSPACE
     cfg = binding.make_config(synth.WORKLOADS["tiny"])
