@@ -93,9 +93,9 @@ typedef struct il_config {
   int32_t dtype;                /* il_dtype                                          */
   int32_t route;                /* il_route                                          */
   float ln_eps;                 /* e.g. 1e-5                                         */
-  int32_t head_chunk;           /* token rows per head chunk (0 = library default: all rows up to
-                                   4096, halved until the tile is below 2 GiB); only a
-                                   [head_chunk, vocab] logits tile ever exists          */
+  int32_t head_chunk;           /* token rows per head chunk (0 = library default: half the
+                                   rows, at most 2048, halved until the tile is below 2 GiB);
+                                   only a [head_chunk, vocab] logits tile ever exists      */
   int32_t profile;              /* 0: off.  1: HIP event times per kernel class (read with
                                    il_profile_read, interlock_test.h); everything then runs on
                                    il_config.stream alone.  2: the step runs exactly as with 0

@@ -744,12 +744,12 @@ int il_init(il_config *cfg, il_ctx **out) {
   }
   int nc = cfg->head_chunk;
   if (nc == 0) {
-    // default: all rows in one chunk up to 4096 (one store of the head matrix's gradient instead of
-    // read-modify-write passes per chunk, fewer partial rounds of tiles), halved until the logits
-    // tile is addressable (below 2 GiB)
-    nc = std::min(c->N, 4096);
+    // default: half the rows, at most 2048, so that logits / probabilities never exist for all tokens
+    // at once; halved until the tile is addressable (below 2 GiB)
+    nc = std::min(c->N / 2, 2048);
     while (nc > 64 && (unsigned long long)nc * c->V * c->eb >= 0x7FFFFFFFull) nc /= 2;
     if (cfg->dtype == IL_BF16) nc = std::max((nc / 64) * 64, 64);
+    if (nc < 1) nc = c->N;
   }
   c->Nc = std::min(nc, c->N);
   if ((unsigned long long)c->Nc * c->V * c->eb >= 0x7FFFFFFFull) {  // the logits tile is a GEMM operand too

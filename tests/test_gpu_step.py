@@ -216,7 +216,7 @@ def test_bf16_reduced_small():
 @pytest.mark.parametrize("head_chunk", [64, 192])          # 256 token rows: 4 equal chunks; 192 + a ragged 64
 def test_bf16_head_in_several_chunks(head_chunk):
     """The head of the bf16 path over several token chunks: statistics, in-place dlogits and dx per chunk,
-    the head matrix's gradient accumulated over the chunks (the default is one chunk of up to 4096 rows)."""
+    the head matrix's gradient accumulated over the chunks, equal and ragged (the default, half the rows, gives two)."""
     w = _small_q()
     say("case bf16 head_chunk =", head_chunk)
     got, ref = run_both(w, seed=4, head_chunk=head_chunk)
