@@ -32,9 +32,9 @@ PEAK_HBM_GBS = 8000.0
 # profiles/traffic_<workload>.md.  bench.py cannot run the profiler on itself, so the figures are
 # carried here for the workloads they were measured on and are null for any other.
 MEASURED_TRAFFIC = {
-    "small_bf16_n2": 42.92e6,   # 32.456 MB read + 10.464 MB written per launch, 1344 launches (1.82 x)
-    "large_bf16_n2": 460.77e6,  # 375.59 MB read + 85.17 MB written per launch, 4104 launches (2.17 x algorithmic)
-    "medium_bf16_n2": 180.80e6,  # 143.98 + 36.82 MB, 2736 launches (1.93 x)
+    "small_bf16_n2": 41.98e6,   # 32.190 MB read + 9.788 MB written per launch, 1536 launches (1.85 x)
+    "large_bf16_n2": 478.98e6,  # 390.00 MB read + 88.97 MB written per launch, 4320 launches (2.15 x algorithmic)
+    "medium_bf16_n2": 179.40e6,  # 140.98 + 38.42 MB, 2880 launches (1.88 x)
     "many_head_bf16_n3": 238.28e6,  # 190.65 + 47.63 MB, 2880 launches (1.99 x)
 }
 
