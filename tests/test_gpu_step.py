@@ -233,6 +233,16 @@ def test_bf16_sequence_lengths_off_the_attention_tiles(T, H):
     say("worst", summary(compare(w, got, ref, f"T={T} H={H}")))
 
 
+def test_bf16_attention_grid_with_a_partial_round_of_balanced_tiles():
+    """5 causal tiles x 128 (batch, head) pairs: every XCD's list of 80 attention workgroups has one full
+    round of 64 (longest first, shortest behind them in opposite order) and a remainder of 16 in plain
+    descending order - both branches of the tile assignment, with an odd number of tile lengths."""
+    w = synth.Workload("bal", "bf16", K=1, L=1, d=256, H=4, m=256, V=256, B=32, T=640, n=1)
+    say("case bf16 balanced attention tiles, grid 5 x 128")
+    got, ref = run_both(w, seed=9)
+    say("worst", summary(compare(w, got, ref, "attention grid 5x128")))
+
+
 @pytest.mark.parametrize("route,n", [("mean_local_far", 3), ("far_head", 2)])
 def test_bf16_paper_routes(route, n):
     """The paper's two routings in bf16 (stacked streams, several runs per component, scaled sums)."""
