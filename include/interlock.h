@@ -119,6 +119,7 @@ typedef struct il_config {
  * with the required sizes, *out is left NULL and IL_E_WORKSPACE is returned.
  * Limits (IL_E_SHAPE otherwise): d_model a multiple of n_heads with head width
  * d_model / n_heads in {16, 32, 64, 128}, or 256 in bf16 mode; d_model <= 2048; batch*seq <= 2^24; vocab <= 2^24;
+ * batch*n_heads <= 65535;
  * in bf16 mode d_model, d_mlp and vocab multiples of 8, batch*seq and head_chunk multiples of
  * 64.  At most 16 merged gradient streams may be live at one component.  Every GEMM operand stays
  * below 2 GiB: streams * batch*seq * max(3 d_model, d_mlp), d_model * vocab, head_chunk * vocab

@@ -683,6 +683,7 @@ int validate(const il_config *cfg) {
   if (cfg->d_model > 2048) return IL_E_SHAPE;
   const long long N = (long long)cfg->batch * cfg->seq;
   if (N > (1 << 24) || (long long)cfg->vocab > (1 << 24)) return IL_E_SHAPE;
+  if ((long long)cfg->batch * cfg->n_heads > 65535) return IL_E_SHAPE;  // the attention grids' y extent
   if (cfg->dtype == IL_BF16) {
     if (cfg->d_model % 8 || cfg->d_mlp % 8 || cfg->vocab % 8 || N % 64) return IL_E_SHAPE;
     if (cfg->head_chunk % 64) return IL_E_SHAPE;

@@ -113,6 +113,8 @@ def test_operands_beyond_the_descriptor_range_are_rejected_up_front():
     assert lib.il_init(C.byref(cfg), C.byref(ctx)) == binding.IL_E_SHAPE
     cfg = binding.make_config(ok.with_(B=16, V=1 << 19, n=1), head_chunk=512)           # a smaller tile fits
     assert lib.il_init(C.byref(cfg), C.byref(ctx)) == binding.IL_E_WORKSPACE
+    cfg = binding.make_config(ok.with_(B=8192, T=64, H=8, n=1))                         # attention grid: batch x heads = 65536
+    assert lib.il_init(C.byref(cfg), C.byref(ctx)) == binding.IL_E_SHAPE
     cfg = binding.make_config(synth.WORKLOADS["tiny"])
     cfg.profile = 3
     assert lib.il_init(C.byref(cfg), C.byref(ctx)) == binding.IL_E_ARG
