@@ -409,7 +409,8 @@ def measured_peaks(copy_mib=1024):
     return {"mfma_only_tflops": mf, "mfma_only_frac_of_nominal": mf / PEAK_BF16_TFLOPS,
             "stream_copy_gbs": cp, "stream_copy_frac_of_nominal": cp / PEAK_HBM_GBS,
             "how": f"il_measure_mfma_peak (512 workgroups x 4 wavefronts x 80000 MFMAs 32x32x16 bf16, registers only); "
-                   f"il_measure_copy_peak ({copy_mib} MiB device-to-device, read + written bytes, best of 2 x 10 launches)"}
+                   f"il_measure_copy_peak ({copy_mib} MiB device-to-device, read + written bytes, the better of a plain 16-byte-per-lane copy "
+                   f"and one with four vectors in flight and non-temporal accesses, best of 2 x 10 launches each)"}
 
 
 def config_of(w):

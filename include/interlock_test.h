@@ -67,11 +67,13 @@ int il_test_gemm(int32_t dtype, const void *A, const void *B, int32_t M, int32_t
 int il_measure_mfma_peak(float *scratch, int32_t iters, void *stream, double *tflops_out);
 
 /*
- * Streaming copy dst[0..bytes) = src[0..bytes), 16 bytes per lane, `reps` launches after one warm-up
- * launch, timed with HIP events on `stream` (the call synchronises).  *gbs_out receives
- * (bytes read + bytes written) / time in GB/s.  Each launch reads and writes exactly `bytes`, so it is
- * also the kernel of known traffic against which a profiler's HBM byte counters are scaled.  dst and src
- * are device pointers, 16-byte aligned, bytes a multiple of 16 (IL_E_SHAPE otherwise); they may not overlap.
+ * Streaming copy dst[0..bytes) = src[0..bytes) in two forms, each run for `reps` launches after one
+ * warm-up launch and timed with HIP events on `stream` (the call synchronises): `stream_copy_kernel`
+ * (16 bytes per lane, plain loads and stores) and `stream_copy4_kernel` (four 16-byte vectors in flight
+ * per lane, non-temporal loads and stores).  *gbs_out receives the better (bytes read + bytes written) /
+ * time in GB/s.  Each launch reads and writes exactly `bytes`, so `stream_copy_kernel` is also the kernel
+ * of known traffic against which a profiler's HBM byte counters are scaled.  dst and src are device
+ * pointers, 16-byte aligned, bytes a multiple of 16 (IL_E_SHAPE otherwise); they may not overlap.
  */
 int il_measure_copy_peak(void *dst, const void *src, size_t bytes, int32_t reps, void *stream, double *gbs_out);
 
