@@ -45,9 +45,14 @@ union Frag {
 
 // A [ROWS tokens] x [DH] tile of a token-major matrix, staged as is ([token][dh]) by direct
 // loads (256 threads, 16 bytes each per round).  The 16-byte chunk c of row r sits at chunk
-// position c ^ h(r), h(r) = ((r & 3) << 1) | ((r >> 2) & 1): eight consecutive rows spread over
-// eight positions (row fragments, ds_read_b128) and four consecutive rows over four position
-// pairs (transposing reads of 32 bytes per row), so neither access bank-conflicts.
+// position c ^ h(r).  LDS has 64 banks of 4 bytes: a ds_read_b128 serves 16 lanes (16 rows x 16
+// bytes) per cycle and a transposing ds_read_b64_tr_b16 32 lanes (4 rows x 64 bytes), so h must
+// send 16 consecutive rows to 16 different 16-byte positions of the 256-byte bank span and 4
+// consecutive rows to 4 different 64-byte quarters of it.  Rows of 256 bytes or more all start at
+// bank 0: h(r) = (r & 3) << 2 | (r >> 2) & 3.  Rows of 128 bytes alternate between the two halves
+// of the span by themselves (bit 0 of r): h(r) = bit 1 of r << 2 | bit 2 << 1 | bit 3.  (With the
+// earlier three-bit h(r) = (r & 3) << 1 | (r >> 2) & 1 the LDS counters showed every second cycle
+// of these kernels' LDS activity as a bank conflict.)
 template <int ROWS, int DH>
 struct TokTile {
   static constexpr int RB = DH * 2, CPR = DH / 8, BYTES = ROWS * RB, NLD = BYTES / (256 * 16);
@@ -55,7 +60,10 @@ struct TokTile {
   uint32_t voff[NLD];
   int radd[NLD];
   uint32_t rstride;
-  __device__ static inline int h(int r) { return ((r & 3) << 1) | ((r >> 2) & 1); }
+  __device__ static inline int h(int r) {
+    if constexpr (DH >= 128) return ((r & 3) << 2) | ((r >> 2) & 3);
+    return (((r >> 1) & 1) << 2) | (((r >> 2) & 1) << 1) | ((r >> 3) & 1);
+  }
   // col0: first element column of this head; ld: elements per token row
   __device__ inline void init(int col0, int ld, int t) {
     rstride = (uint32_t)ld * 2u;

@@ -198,7 +198,10 @@ __device__ inline void epilogue_strips(const GemmArgs &g, floatx16 (&acc)[MI][NI
 // LDS image of a tile is fixed and the swizzle is applied on the global side: the thread that
 // fills LDS chunk position p fetches the logical chunk that belongs there.
 //   k-contiguous tile: [row][BKT] (BKT*2 bytes per row), chunk c of row r at c ^ g(r)
-//   k-major tile:      [k][ROWS]  (ROWS*2 bytes per k),  chunk c of k-row k at c ^ 2(k & 3)
+//   k-major tile:      [k][ROWS]  (ROWS*2 bytes per k),  chunk c of k-row k at c ^ KS(k & 3), KS = 4 for k-rows of
+//                      256 bytes or more (all start at bank 0 of the 64 four-byte banks: the four k-rows that one
+//                      cycle of a transposing read touches, 64 bytes each, go to the four quarters of the bank
+//                      span), 2 for 128-byte k-rows (which alternate between the halves of the span by themselves)
 // A k-major fragment is two ds_read_b64_tr_b16: within 16 lanes, lane i points at 4
 // consecutive rows-elements of k-row kb + i/4, column group 4(i%4); the instruction hands
 // lane j the four k values kb..kb+3 of row j - exactly the MFMA operand order.
@@ -210,6 +213,7 @@ struct DmaTile {
   static constexpr int NLD = BYTES / (NT * 16);  // loads per thread per K step
   static_assert(BYTES % (NT * 16) == 0 && NLD >= 1, "tile must divide over the threads");
   static constexpr int RB = KMAJOR ? ROWS * 2 : BKT * 2;  // LDS bytes per row
+  static constexpr int KS = ROWS >= 128 ? 4 : 2;          // k-major swizzle step, in 16-byte chunks
   uint32_t voff[NLD];
   int kadd[NLD];
   uint32_t kstride;
@@ -228,7 +232,7 @@ struct DmaTile {
         kstride = 2;
       } else {
         constexpr int CPR = ROWS / 8;
-        const int krow = p / CPR, chunk = (p % CPR) ^ (2 * (krow & 3));
+        const int krow = p / CPR, chunk = (p % CPR) ^ (KS * (krow & 3));
         kadd[i] = krow;
         voff[i] = row0 + chunk * 8 < rows ? ((uint32_t)krow * ld + row0 + chunk * 8) * 2u : kOob;
         kstride = (uint32_t)ld * 2u;
@@ -269,7 +273,7 @@ struct DmaTile {
       const int g16 = lane >> 4, i = lane & 15;
       const int m = rbase + 16 * (g16 & 1) + 4 * (i & 3);
       const int k = 16 * ks + 8 * (g16 >> 1) + (i >> 2);
-      const int col = (((m >> 3) ^ (2 * (i >> 2))) << 4) + ((m >> 2) & 1) * 8;
+      const int col = (((m >> 3) ^ (KS * (i >> 2))) << 4) + ((m >> 2) & 1) * 8;
       union { short4v h[2]; bf16x8 v; } f;
       f.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
           (__attribute__((address_space(3))) short4v *)(lds + k * RB + col));
