@@ -19,18 +19,6 @@ namespace {
 
 struct AdamScalars { float b1, b2, omb1, omb2, c1, c2, lr, eps; };
 
-// Every array is streamed through exactly once per step: non-temporal accesses (they do not displace
-// cache lines and run ~10 % faster than plain ones on this part).
-typedef float f32x4v __attribute__((ext_vector_type(4)));
-__device__ inline float4 ldnt4(const float *base, size_t i) {
-  const f32x4v v = __builtin_nontemporal_load(reinterpret_cast<const f32x4v *>(base) + i);
-  return make_float4(v.x, v.y, v.z, v.w);
-}
-__device__ inline void stnt4(float *base, size_t i, const float4 &q) {
-  const f32x4v v = {q.x, q.y, q.z, q.w};
-  __builtin_nontemporal_store(v, reinterpret_cast<f32x4v *>(base) + i);
-}
-
 __device__ inline float adam_one(float g, float &m, float &v, float w, const AdamScalars &a) {
   m = a.b1 * m + a.omb1 * g;
   v = a.b2 * v + a.omb2 * g * g;
@@ -49,24 +37,24 @@ __global__ __launch_bounds__(256) void adam_step_kernel(float *__restrict__ w, b
   for (size_t i0 = (size_t)blockIdx.x * 256 + threadIdx.x; i0 < n4; i0 += 2 * stride) {
     const size_t i1 = i0 + stride;
     const bool two = i1 < n4;
-    const float4 g0 = ldnt4(g, i0);
-    float4 m0 = ldnt4(m, i0), v0 = ldnt4(v, i0);
-    float4 w0 = ldnt4(w, i0);
+    const float4 g0 = reinterpret_cast<const float4 *>(g)[i0];
+    float4 m0 = reinterpret_cast<float4 *>(m)[i0], v0 = reinterpret_cast<float4 *>(v)[i0];
+    float4 w0 = reinterpret_cast<float4 *>(w)[i0];
     float4 g1 = g0, m1 = m0, v1 = v0, w1 = w0;
     if (two) {
-      g1 = ldnt4(g, i1);
-      m1 = ldnt4(m, i1);
-      v1 = ldnt4(v, i1);
-      w1 = ldnt4(w, i1);
+      g1 = reinterpret_cast<const float4 *>(g)[i1];
+      m1 = reinterpret_cast<float4 *>(m)[i1];
+      v1 = reinterpret_cast<float4 *>(v)[i1];
+      w1 = reinterpret_cast<float4 *>(w)[i1];
     }
     auto update = [&](const float4 &gg, float4 &mm, float4 &vv, float4 &ww, size_t i) {
       ww.x = adam_one(gg.x, mm.x, vv.x, ww.x, a);
       ww.y = adam_one(gg.y, mm.y, vv.y, ww.y, a);
       ww.z = adam_one(gg.z, mm.z, vv.z, ww.z, a);
       ww.w = adam_one(gg.w, mm.w, vv.w, ww.w, a);
-      stnt4(m, i, mm);
-      stnt4(v, i, vv);
-      stnt4(w, i, ww);
+      reinterpret_cast<float4 *>(m)[i] = mm;
+      reinterpret_cast<float4 *>(v)[i] = vv;
+      reinterpret_cast<float4 *>(w)[i] = ww;
       if constexpr (BF) {
         uint2 q;
         q.x = pack_bf16x2(ww.x, ww.y);
